@@ -1,0 +1,209 @@
+/*
+ * propd.h - C ABI of the MI355X token-tree verification library.
+ *
+ * The library implements the verification step of ProPD's parallel decoding
+ * (arXiv 2402.13485): tree-masked attention, the early-pruning pass and greedy
+ * acceptance, as HIP kernels for gfx950.  Plain C99: pointers and sizes only.
+ *
+ * Common rules for every entry point
+ *   - Pointers named in a parameter list are DEVICE pointers unless the comment
+ *     says "host".  The caller owns every buffer, before and after the call; the
+ *     library allocates nothing, frees nothing and keeps no pointer.
+ *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL =
+ *     the default stream).  No entry point synchronises with the host or copies
+ *     between host and device; outputs are valid once the stream reaches the end
+ *     of the enqueued work.  `workspace` is scratch for the duration of that work
+ *     and must not be shared by calls that may overlap on different streams.
+ *   - Scalars are validated on the host: a bad scalar, a NULL required pointer or
+ *     a short workspace returns an error code and enqueues nothing.  The content
+ *     of device arrays is not validated: a tree whose parent array is not
+ *     topological (parent[i] < i), or a mask that does not belong to the parent
+ *     array, gives unspecified results, but never an out-of-bounds access
+ *     (indices read from device arrays are range-checked in the kernels).
+ *   - Tensors are dense and row-major with the innermost dimension contiguous;
+ *     base pointers must be 16-byte aligned.
+ *   - Trees: node 0 of every sequence is the root, i.e. the token the model has
+ *     already fixed; it counts towards T, is never pruned and is always accepted.
+ *     Nodes are stored in a topological (for instance breadth-first) order.
+ *     Per-sequence slots have T_max entries; entries at or beyond n_nodes[b] are
+ *     padding: never read as data, and written only where a comment says so.
+ */
+#ifndef PROPD_H
+#define PROPD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Entry points are the only symbols the shared library exports. */
+#if defined(__GNUC__)
+#define PROPD_API __attribute__((visibility("default")))
+#else
+#define PROPD_API
+#endif
+
+typedef enum {
+  PROPD_OK = 0,
+  PROPD_ERR_INVALID_ARG = 1, /* a scalar out of range or a required pointer is NULL */
+  PROPD_ERR_UNSUPPORTED = 2, /* a legal request this build has no kernel for        */
+  PROPD_ERR_WORKSPACE = 3,   /* workspace NULL or smaller than propd_workspace_bytes */
+  PROPD_ERR_DEVICE = 4       /* the HIP runtime refused a launch                    */
+} propd_status;
+
+typedef enum { PROPD_F32 = 0, PROPD_BF16 = 1 } propd_dtype;
+
+/* Largest tree, root included.  A node's ancestor set is a 128-bit set, two
+ * uint64 words, word 0 holding nodes 0..63. */
+#define PROPD_MAX_TREE 128
+
+/* A batch of token trees (Section 2: candidates organised as a tree that shares
+ * common prefixes; node = one candidate token at one future position). */
+typedef struct propd_tree {
+  int32_t B;               /* sequences, >= 1                                         */
+  int32_t T_max;           /* slot size, 1..PROPD_MAX_TREE                            */
+  const int32_t *n_nodes;  /* [B]          T_b in 1..T_max                            */
+  const int32_t *parent;   /* [B,T_max]    parent[0] = -1, 0 <= parent[i] < i         */
+  const int32_t *token;    /* [B,T_max]    candidate token id of each node            */
+  const int32_t *depth;    /* [B,T_max]    edges to the root, depth[0] = 0            */
+  const uint64_t *anc;     /* [B,T_max,2]  ancestor-or-self set: the cached tree mask */
+} propd_tree;
+
+/* Same fields, writable: where a call produces a tree. */
+typedef struct propd_tree_out {
+  int32_t *n_nodes;
+  int32_t *parent;
+  int32_t *token;
+  int32_t *depth;
+  uint64_t *anc;
+} propd_tree_out;
+
+/* A per-node row tensor that continues past the pruning point and has to be
+ * narrowed to the surviving nodes.  It is viewed as [B, outer, T_max] rows of
+ * row_bytes bytes; hidden states [B,T_max,Hd] have outer = 1, tree K or V
+ * [B,H,T_max,d] have outer = H.  Strides are in bytes and apply to src and dst. */
+typedef struct propd_payload {
+  const void *src;         /* device                                                  */
+  void *dst;               /* device, must not overlap src                            */
+  size_t row_bytes;
+  int64_t outer;
+  int64_t stride_b, stride_outer, stride_t;
+} propd_payload;
+
+/*
+ * Build the cached tree mask from parent pointers (Section 2, "Verification";
+ * Section 4.1, "Implementation Optimization": the mask lives on the GPU).
+ *   anc[b,i]  = set of nodes on the root path of i, i included
+ *   depth[b,i] = number of edges from i to the root
+ * Padding slots get anc = 0 and depth = -1.  depth may be NULL.
+ */
+PROPD_API propd_status propd_tree_mask(int32_t B, int32_t T_max, const int32_t *n_nodes,
+                             const int32_t *parent, int32_t *depth, uint64_t *anc,
+                             void *hip_stream);
+
+/*
+ * Tree-masked attention (Section 2, "Verification"; Figure 2(b,c)).  For every
+ * sequence b, head h and tree node i < T_b:
+ *     out[b,h,i,:] = softmax_j( scale * <q[b,h,i,:], k_j> ) . v_j
+ * where j runs over all L_b = seq_lens[b] cached prefix tokens and over the tree
+ * nodes in anc[b,i] (the node's own candidate sequence, itself included).
+ *
+ *   dt        PROPD_BF16: tensors are bf16, d must be 128; scores, softmax and
+ *             the output accumulation are fp32, the result is rounded to bf16.
+ *             PROPD_F32: tensors are fp32, d in {64, 128}, fp32 throughout.
+ *   q, k_tree, v_tree, out   [B,H,T_max,d]
+ *   k_cache, v_cache         [B,H,L_max,d]; rows >= L_b are never used
+ *   seq_lens  [B], 0 <= L_b <= L_max
+ *   tree      n_nodes and anc are read (token, parent, depth may be NULL)
+ *   out       rows i >= T_b are left untouched
+ *   workspace propd_workspace_bytes(PROPD_WS_TREE_ATTENTION, ...) bytes
+ */
+PROPD_API propd_status propd_tree_attention(const propd_tree *tree, propd_dtype dt, int32_t H, int32_t d,
+                                  float scale, const void *q, const void *k_cache,
+                                  const void *v_cache, const void *k_tree, const void *v_tree,
+                                  const int32_t *seq_lens, int32_t L_max, void *out,
+                                  void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Early pruning (Section 4.1, "Pruning Process" and "Implementation
+ * Optimization").
+ *   1. Early head: for every node p that has children, scores over the vocabulary
+ *      z_p = head_weight . hidden_states[b,p,:]  (fp32 accumulation).
+ *   2. Top-k test: child c of p fails unless its token is among the top_k best
+ *      scores of z_p.  Membership is decided by counting,
+ *      rank_c = #{v : z_p[v] > z_p[tok_c]} + #{v < tok_c : z_p[v] == z_p[tok_c]},
+ *      fail_c = rank_c >= top_k.  top_k >= vocab prunes nothing.
+ *   3. Branch elimination: a node survives iff no node of its root path failed.
+ *   4. Survivors are compacted in order; the cached mask is subsampled to the
+ *      surviving rows and columns; the listed row payloads are gathered.
+ *
+ *   hidden_states [B,T_max,hidden]  layer-n hidden state of every tree token
+ *   head_weight   [vocab,hidden]    weight of the bias-free early head, one row
+ *                                   per vocabulary entry (nn.Linear layout)
+ *   dt            PROPD_BF16 (hidden must be a multiple of 64) or PROPD_F32
+ *   tree          all five arrays are read; token ids outside [0, vocab) fail
+ * Outputs (each fully written, padding included; any may NOT alias an input):
+ *   keep_bits  [B,2]      bit i set iff node i survives
+ *   new_index  [B,T_max]  position of node i among survivors, -1 if pruned/padding
+ *   orig_index [B,T_max]  old index of survivor j, -1 for j >= n_kept[b]
+ *   n_kept     [B]        number of survivors (also written to tree_out->n_nodes)
+ *   cu_nodes   [B+1]      exclusive prefix sum of n_kept (ragged offsets)
+ *   tree_out   compacted tree in the same padded layout, survivors first:
+ *              parent re-indexed, token and depth copied, anc subsampled;
+ *              slots >= n_kept[b] hold -1 (anc: 0)
+ *   rank_out   [B,T_max] or NULL: rank_c as counted (root 0, padding -1); ranks of
+ *              near-equal scores may differ from a higher-precision evaluation
+ *   payloads   host array of n_payloads descriptors (0..PROPD_MAX_PAYLOADS, read
+ *              during the call only).  Row (b,o,orig_index[b,j]) of src is copied
+ *              to row (b,o,j) of dst for j < n_kept[b]; other dst rows are untouched.
+ *   workspace  propd_workspace_bytes(PROPD_WS_EARLY_PRUNE, ...) bytes
+ */
+#define PROPD_MAX_PAYLOADS 8
+PROPD_API propd_status propd_early_prune(const propd_tree *tree, propd_dtype dt, int32_t hidden,
+                               int32_t vocab, int32_t top_k, const void *hidden_states,
+                               const void *head_weight, uint64_t *keep_bits, int32_t *new_index,
+                               int32_t *orig_index, int32_t *n_kept, int32_t *cu_nodes,
+                               const propd_tree_out *tree_out, int32_t *rank_out,
+                               int32_t n_payloads, const propd_payload *payloads,
+                               void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Greedy acceptance (Section 3, "acceptance length"; Section 5.1: greedy
+ * decoding, so the output equals the large model's own).  With
+ * g_i = argmax_v logits[b,i,v] (lowest id among equal maxima), a child is
+ * accepted iff its token equals g at its parent and its parent is accepted; the
+ * root is always accepted.  The result is the deepest accepted node (lowest
+ * index among equally deep ones).
+ *
+ *   logits      [B,T_max,vocab], dt = PROPD_BF16 or PROPD_F32; rows >= T_b unused
+ *   tree        n_nodes, parent, token, anc are read
+ *   accept_len  [B]              nodes on the accepted path, root included (>= 1)
+ *   accept_path [B,path_stride]  node indices (of the tree passed in) root first,
+ *                                -1 padded; entries beyond path_stride are dropped
+ *   next_token  [B]              g at the last accepted node
+ *   workspace   propd_workspace_bytes(PROPD_WS_ACCEPT_PATH, ...) bytes
+ */
+PROPD_API propd_status propd_accept_path(const propd_tree *tree, propd_dtype dt, int32_t vocab,
+                               const void *logits, int32_t *accept_len, int32_t *accept_path,
+                               int32_t path_stride, int32_t *next_token, void *workspace,
+                               size_t workspace_bytes, void *hip_stream);
+
+/* Workspace size in bytes for one call with these dimensions (arguments a call
+ * does not have are ignored).  Pure host arithmetic.  Returns 0 for a bad `which`. */
+typedef enum {
+  PROPD_WS_TREE_ATTENTION = 0,
+  PROPD_WS_EARLY_PRUNE = 1,
+  PROPD_WS_ACCEPT_PATH = 2
+} propd_ws_kind;
+PROPD_API size_t propd_workspace_bytes(propd_ws_kind which, int32_t B, int32_t T_max, int32_t H, int32_t d,
+                             int32_t L_max, int32_t hidden, int32_t vocab);
+
+/* Static, NUL-terminated description of a status code. */
+PROPD_API const char *propd_status_string(propd_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PROPD_H */

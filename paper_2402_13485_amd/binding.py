@@ -1,0 +1,272 @@
+"""Thin Python binding of the C ABI in ``include/propd.h``.
+
+Argument marshalling only: every step of the verification path runs in the HIP
+kernels of ``libpropd.so``.  PyTorch tensors supply device memory and the current
+stream; nothing here computes on them.  There is no CPU fallback: if the library
+is missing or cannot be loaded, importing the entry points raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpropd.so")
+
+PROPD_F32, PROPD_BF16 = 0, 1
+WS_TREE_ATTENTION, WS_EARLY_PRUNE, WS_ACCEPT_PATH = 0, 1, 2
+MAX_TREE = 128
+MAX_PAYLOADS = 8
+
+EXPORTS = ("propd_tree_mask", "propd_tree_attention", "propd_early_prune", "propd_accept_path",
+           "propd_workspace_bytes", "propd_status_string")
+
+
+class _Tree(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("T_max", ctypes.c_int32),
+                ("n_nodes", ctypes.c_void_p), ("parent", ctypes.c_void_p),
+                ("token", ctypes.c_void_p), ("depth", ctypes.c_void_p), ("anc", ctypes.c_void_p)]
+
+
+class _TreeOut(ctypes.Structure):
+    _fields_ = [("n_nodes", ctypes.c_void_p), ("parent", ctypes.c_void_p),
+                ("token", ctypes.c_void_p), ("depth", ctypes.c_void_p), ("anc", ctypes.c_void_p)]
+
+
+class _Payload(ctypes.Structure):
+    _fields_ = [("src", ctypes.c_void_p), ("dst", ctypes.c_void_p), ("row_bytes", ctypes.c_size_t),
+                ("outer", ctypes.c_int64), ("stride_b", ctypes.c_int64),
+                ("stride_outer", ctypes.c_int64), ("stride_t", ctypes.c_int64)]
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libpropd.so (built in-tree by ``build.py``); raise if it is not there."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2402_13485_amd.build` "
+            "(there is no fallback implementation)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+    lib.propd_tree_mask.restype = ctypes.c_int
+    lib.propd_tree_mask.argtypes = [i32, i32, vp, vp, vp, vp, vp]
+    lib.propd_tree_attention.restype = ctypes.c_int
+    lib.propd_tree_attention.argtypes = [ctypes.POINTER(_Tree), ctypes.c_int, i32, i32,
+                                         ctypes.c_float, vp, vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
+    lib.propd_early_prune.restype = ctypes.c_int
+    lib.propd_early_prune.argtypes = [ctypes.POINTER(_Tree), ctypes.c_int, i32, i32, i32, vp, vp,
+                                      vp, vp, vp, vp, vp, ctypes.POINTER(_TreeOut), vp, i32,
+                                      ctypes.POINTER(_Payload), vp, sz, vp]
+    lib.propd_accept_path.restype = ctypes.c_int
+    lib.propd_accept_path.argtypes = [ctypes.POINTER(_Tree), ctypes.c_int, i32, vp, vp, vp, i32, vp,
+                                      vp, sz, vp]
+    lib.propd_workspace_bytes.restype = sz
+    lib.propd_workspace_bytes.argtypes = [ctypes.c_int, i32, i32, i32, i32, i32, i32, i32]
+    lib.propd_status_string.restype = ctypes.c_char_p
+    lib.propd_status_string.argtypes = [ctypes.c_int]
+    _lib = lib
+    return lib
+
+
+class PropdError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        msg = load_library().propd_status_string(code).decode()
+        super().__init__(f"{where}: {msg} (status {code})")
+
+
+def _check(code: int, where: str) -> None:
+    if code != 0:
+        raise PropdError(code, where)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _dev(t: torch.Tensor, dtype: torch.dtype, name: str) -> torch.Tensor:
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise TypeError(f"{name}: need a contiguous {dtype} tensor in GPU memory")
+    return t
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return PROPD_BF16
+    if t.dtype == torch.float32:
+        return PROPD_F32
+    raise TypeError(f"tensor dtype must be bfloat16 or float32, got {t.dtype}")
+
+
+@dataclass
+class Tree:
+    """Device-resident batch of token trees (fields as in ``propd_tree``)."""
+    n_nodes: torch.Tensor                 # int32 [B]
+    parent: torch.Tensor                  # int32 [B,T_max]
+    token: Optional[torch.Tensor] = None  # int32 [B,T_max]
+    depth: Optional[torch.Tensor] = None  # int32 [B,T_max]
+    anc: Optional[torch.Tensor] = None    # int64 [B,T_max,2] holding the uint64 bit sets
+
+    @property
+    def B(self) -> int:
+        return self.parent.shape[0]
+
+    @property
+    def T_max(self) -> int:
+        return self.parent.shape[1]
+
+    def _c(self) -> _Tree:
+        return _Tree(self.B, self.T_max, _ptr(self.n_nodes), _ptr(self.parent), _ptr(self.token),
+                     _ptr(self.depth), _ptr(self.anc))
+
+
+def workspace_bytes(which: int, B: int, T_max: int, H: int = 0, d: int = 0, L_max: int = 0,
+                    hidden: int = 0, vocab: int = 0) -> int:
+    return int(load_library().propd_workspace_bytes(which, B, T_max, H, d, L_max, hidden, vocab))
+
+
+def _workspace(nbytes: int, device, workspace: Optional[torch.Tensor]) -> torch.Tensor:
+    if workspace is not None:
+        if workspace.numel() * workspace.element_size() < nbytes:
+            raise ValueError("workspace tensor too small")
+        return workspace
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+
+
+def propd_tree_mask(n_nodes: torch.Tensor, parent: torch.Tensor):
+    """-> (depth int32 [B,T_max], anc int64 [B,T_max,2])"""
+    _dev(n_nodes, torch.int32, "n_nodes")
+    _dev(parent, torch.int32, "parent")
+    B, T_max = parent.shape
+    depth = torch.empty((B, T_max), dtype=torch.int32, device=parent.device)
+    anc = torch.empty((B, T_max, 2), dtype=torch.int64, device=parent.device)
+    _check(load_library().propd_tree_mask(B, T_max, _ptr(n_nodes), _ptr(parent), _ptr(depth),
+                                          _ptr(anc), _stream()), "propd_tree_mask")
+    return depth, anc
+
+
+def propd_tree_attention(tree: Tree, q, k_cache, v_cache, k_tree, v_tree, seq_lens, scale: float,
+                         out: Optional[torch.Tensor] = None,
+                         workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    dt = _dt(q)
+    B, H, T_max, d = q.shape
+    L_max = k_cache.shape[2]
+    for name, t, shape in (("q", q, (B, H, T_max, d)), ("k_cache", k_cache, (B, H, L_max, d)),
+                           ("v_cache", v_cache, (B, H, L_max, d)),
+                           ("k_tree", k_tree, (B, H, T_max, d)),
+                           ("v_tree", v_tree, (B, H, T_max, d))):
+        _dev(t, q.dtype, name)
+        if tuple(t.shape) != shape:
+            raise ValueError(f"{name}: expected shape {shape}, got {tuple(t.shape)}")
+    _dev(seq_lens, torch.int32, "seq_lens")
+    if tree.B != B or tree.T_max != T_max:
+        raise ValueError("tree and q disagree on B or T_max")
+    if out is None:
+        out = torch.empty_like(q)
+    ws = _workspace(workspace_bytes(WS_TREE_ATTENTION, B, T_max, H, d, L_max), q.device, workspace)
+    c_tree = tree._c()
+    _check(load_library().propd_tree_attention(
+        ctypes.byref(c_tree), dt, H, d, scale, _ptr(q), _ptr(k_cache) if L_max else None,
+        _ptr(v_cache) if L_max else None, _ptr(k_tree), _ptr(v_tree), _ptr(seq_lens), L_max,
+        _ptr(out), _ptr(ws), ws.numel() * ws.element_size(), _stream()), "propd_tree_attention")
+    return out
+
+
+@dataclass
+class PruneResult:
+    keep_bits: torch.Tensor   # int64 [B,2]
+    new_index: torch.Tensor   # int32 [B,T_max]
+    orig_index: torch.Tensor  # int32 [B,T_max]
+    n_kept: torch.Tensor      # int32 [B]
+    cu_nodes: torch.Tensor    # int32 [B+1]
+    tree: Tree                # compacted tree
+    rank: Optional[torch.Tensor]
+    payloads: list
+
+
+def propd_early_prune(tree: Tree, hidden_states: torch.Tensor, head_weight: torch.Tensor,
+                      top_k: int, payloads: Sequence[torch.Tensor] = (),
+                      payload_out: Optional[Sequence[torch.Tensor]] = None,
+                      want_rank: bool = False,
+                      workspace: Optional[torch.Tensor] = None) -> PruneResult:
+    """``payloads`` are tensors shaped [B,T_max,C] or [B,outer,T_max,C] to narrow to survivors."""
+    dt = _dt(hidden_states)
+    B, T_max, hidden = hidden_states.shape
+    vocab = head_weight.shape[0]
+    _dev(hidden_states, hidden_states.dtype, "hidden_states")
+    _dev(head_weight, hidden_states.dtype, "head_weight")
+    if tuple(head_weight.shape) != (vocab, hidden):
+        raise ValueError("head_weight must be [vocab, hidden]")
+    if tree.B != B or tree.T_max != T_max:
+        raise ValueError("tree and hidden_states disagree on B or T_max")
+    dev = hidden_states.device
+    i32 = dict(dtype=torch.int32, device=dev)
+    res = PruneResult(
+        keep_bits=torch.empty((B, 2), dtype=torch.int64, device=dev),
+        new_index=torch.empty((B, T_max), **i32), orig_index=torch.empty((B, T_max), **i32),
+        n_kept=torch.empty(B, **i32), cu_nodes=torch.empty(B + 1, **i32),
+        tree=Tree(n_nodes=torch.empty(B, **i32), parent=torch.empty((B, T_max), **i32),
+                  token=torch.empty((B, T_max), **i32), depth=torch.empty((B, T_max), **i32),
+                  anc=torch.empty((B, T_max, 2), dtype=torch.int64, device=dev)),
+        rank=torch.empty((B, T_max), **i32) if want_rank else None, payloads=[])
+    descs = (_Payload * max(len(payloads), 1))()
+    for n, src in enumerate(payloads):
+        if not src.is_cuda or not src.is_contiguous() or src.dim() not in (3, 4):
+            raise TypeError("payload: need a contiguous GPU tensor [B,T_max,C] or [B,outer,T_max,C]")
+        outer = 1 if src.dim() == 3 else src.shape[1]
+        if src.shape[0] != B or src.shape[-2] != T_max:
+            raise ValueError("payload shape does not match the tree")
+        dst = payload_out[n] if payload_out is not None else torch.empty_like(src)
+        if dst.shape != src.shape or dst.dtype != src.dtype or not dst.is_contiguous():
+            raise ValueError("payload_out must match the payload")
+        row_bytes = src.shape[-1] * src.element_size()
+        descs[n] = _Payload(src.data_ptr(), dst.data_ptr(), row_bytes, outer,
+                            outer * T_max * row_bytes, T_max * row_bytes, row_bytes)
+        res.payloads.append(dst)
+    t_out = _TreeOut(_ptr(res.tree.n_nodes), _ptr(res.tree.parent), _ptr(res.tree.token),
+                     _ptr(res.tree.depth), _ptr(res.tree.anc))
+    ws = _workspace(workspace_bytes(WS_EARLY_PRUNE, B, T_max, hidden=hidden, vocab=vocab), dev,
+                    workspace)
+    c_tree = tree._c()
+    _check(load_library().propd_early_prune(
+        ctypes.byref(c_tree), dt, hidden, vocab, top_k, _ptr(hidden_states), _ptr(head_weight),
+        _ptr(res.keep_bits), _ptr(res.new_index), _ptr(res.orig_index), _ptr(res.n_kept),
+        _ptr(res.cu_nodes), ctypes.byref(t_out), _ptr(res.rank), len(payloads), descs, _ptr(ws),
+        ws.numel() * ws.element_size(), _stream()), "propd_early_prune")
+    return res
+
+
+def propd_accept_path(tree: Tree, logits: torch.Tensor, path_stride: Optional[int] = None,
+                      workspace: Optional[torch.Tensor] = None):
+    """-> (accept_len int32 [B], accept_path int32 [B,path_stride], next_token int32 [B])"""
+    dt = _dt(logits)
+    B, T_max, vocab = logits.shape
+    _dev(logits, logits.dtype, "logits")
+    if tree.B != B or tree.T_max != T_max:
+        raise ValueError("tree and logits disagree on B or T_max")
+    if path_stride is None:
+        path_stride = T_max
+    dev = logits.device
+    accept_len = torch.empty(B, dtype=torch.int32, device=dev)
+    path = torch.empty((B, path_stride), dtype=torch.int32, device=dev)
+    next_token = torch.empty(B, dtype=torch.int32, device=dev)
+    ws = _workspace(workspace_bytes(WS_ACCEPT_PATH, B, T_max, vocab=vocab), dev, workspace)
+    c_tree = tree._c()
+    _check(load_library().propd_accept_path(
+        ctypes.byref(c_tree), dt, vocab, _ptr(logits), _ptr(accept_len), _ptr(path), path_stride,
+        _ptr(next_token), _ptr(ws), ws.numel() * ws.element_size(), _stream()),
+        "propd_accept_path")
+    return accept_len, path, next_token

@@ -1,0 +1,567 @@
+// Early pruning of the token tree (Section 4.1: "Pruning Process" and
+// "Implementation Optimization").
+//
+// Kernel chain, all on the caller's stream, no host round trip:
+//   parent_rows_kernel    per sequence: which nodes have children (only those
+//                         need early-head scores), compacted by wave ballot
+//   row_table_kernel      prefix sum over sequences -> global row table
+//   early_head_bf16_kernel  scores z = hidden[parent rows] . head_weight^T as a
+//                         bf16 MFMA GEMM with fp32 accumulation (M = parent rows,
+//                         N = vocabulary, K = hidden); fp32 scores go to scratch
+//   early_head_f32_kernel plain fp32 variant
+//   rank_count_kernel     per parent row: rank of every child's token by
+//                         counting scores that beat it (the top-k membership test)
+//   prune_compact_kernel  per sequence: fail bits by ballot, branch elimination
+//                         by testing the cached ancestor bitset against the fail
+//                         bits, order-preserving compaction by prefix popcount,
+//                         mask subsampling by bit extraction
+//   cu_nodes_kernel       exclusive prefix sum of survivor counts
+//   gather_rows_kernel    survivor rows of the listed payload tensors
+#include "common.h"
+
+namespace propd {
+
+// ------------------------------------------------------------------------------------
+// scratch layout
+// ------------------------------------------------------------------------------------
+struct PruneScratch {
+  int32_t *rank;        // [B*T_max]
+  int32_t *n_par;       // [B]
+  int32_t *local_list;  // [B*T_max]  per sequence: nodes with children, ascending
+  int32_t *row_src;     // [B*T_max]  global row -> b*T_max + node
+  int32_t *row_base;    // [B+1]      exclusive prefix of n_par; [B] = total rows
+  float *scores;        // [row_cap * score_pitch]
+  size_t row_cap, score_pitch, total_bytes;
+};
+
+static PruneScratch carve_scratch(void *base, int B, int T_max, int vocab) {
+  PruneScratch s;
+  char *p = reinterpret_cast<char *>(base);
+  size_t off = 0;
+  const size_t nt = (size_t)B * T_max;
+  auto take = [&](size_t bytes) {
+    char *q = p ? p + off : nullptr;
+    off += align_up(bytes, 256);
+    return q;
+  };
+  s.rank = reinterpret_cast<int32_t *>(take(nt * 4));
+  s.n_par = reinterpret_cast<int32_t *>(take((size_t)B * 4));
+  s.local_list = reinterpret_cast<int32_t *>(take(nt * 4));
+  s.row_src = reinterpret_cast<int32_t *>(take(nt * 4));
+  s.row_base = reinterpret_cast<int32_t *>(take((size_t)(B + 1) * 4));
+  s.row_cap = (size_t)B * (T_max > 1 ? T_max - 1 : 1);  // a node with children is not a leaf
+  s.score_pitch = align_up((size_t)vocab, 4);
+  s.scores = reinterpret_cast<float *>(take(s.row_cap * s.score_pitch * 4));
+  s.total_bytes = off;
+  return s;
+}
+
+size_t early_prune_workspace_bytes(int B, int T_max, int vocab) {
+  return carve_scratch(nullptr, B, T_max, vocab).total_bytes;
+}
+
+// ------------------------------------------------------------------------------------
+// which nodes need scores
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(PROPD_MAX_TREE) void parent_rows_kernel(
+    int T_max, const int32_t *__restrict__ n_nodes, const int32_t *__restrict__ parent,
+    int32_t *__restrict__ n_par, int32_t *__restrict__ local_list, int32_t *__restrict__ rank) {
+  const int b = blockIdx.x, i = threadIdx.x;
+  int T = n_nodes[b];
+  T = T < 1 ? 1 : (T > T_max ? T_max : T);
+  __shared__ int s_has_child[PROPD_MAX_TREE];
+  __shared__ int s_wave_count[2];
+  s_has_child[i] = 0;
+  __syncthreads();
+  if (i > 0 && i < T) {
+    const int p = parent[(size_t)b * T_max + i];
+    if (p >= 0 && p < i) s_has_child[p] = 1;  // same value from every child: benign
+  }
+  __syncthreads();
+  const bool is_par = i < T && s_has_child[i] != 0;
+  const uint64_t bal = __ballot(is_par);
+  if ((i & 63) == 0) s_wave_count[i >> 6] = __popcll(bal);
+  __syncthreads();
+  const int before = (i >= 64 ? s_wave_count[0] : 0) + __popcll(bal & ((1ull << (i & 63)) - 1ull));
+  if (is_par) local_list[(size_t)b * T_max + before] = i;
+  if (i == 0) n_par[b] = s_wave_count[0] + s_wave_count[1];
+  // ranks default to 0 (root; everything when nothing is scored), padding to -1
+  if (i < T_max) rank[(size_t)b * T_max + i] = i < T ? 0 : -1;
+}
+
+constexpr int kScanThreads = 256;
+
+// Exclusive prefix sum of in[0..n) into out[0..n], out[n] = total.  One workgroup.
+__device__ void block_exclusive_scan(const int32_t *__restrict__ in, int32_t *__restrict__ out,
+                                     int n) {
+  __shared__ int s_part[kScanThreads];
+  const int tid = threadIdx.x;
+  const int per = (n + kScanThreads - 1) / kScanThreads;
+  const int lo = tid * per, hi = (lo + per < n) ? lo + per : n;
+  int sum = 0;
+  for (int x = lo; x < hi; ++x) sum += in[x];
+  s_part[tid] = sum;
+  __syncthreads();
+  if (tid == 0) {
+    int run = 0;
+    for (int t = 0; t < kScanThreads; ++t) {
+      const int v = s_part[t];
+      s_part[t] = run;
+      run += v;
+    }
+    out[n] = run;
+  }
+  __syncthreads();
+  int run = s_part[tid];
+  for (int x = lo; x < hi; ++x) {
+    const int v = in[x];
+    out[x] = run;
+    run += v;
+  }
+}
+
+__global__ __launch_bounds__(kScanThreads) void row_table_kernel(
+    int B, int T_max, const int32_t *__restrict__ n_par, const int32_t *__restrict__ local_list,
+    int32_t *__restrict__ row_base, int32_t *__restrict__ row_src) {
+  block_exclusive_scan(n_par, row_base, B);
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < B * T_max; idx += kScanThreads) {
+    const int b = idx / T_max, r = idx - b * T_max;
+    if (r < n_par[b]) row_src[row_base[b] + r] = b * T_max + local_list[idx];
+  }
+}
+
+__global__ __launch_bounds__(kScanThreads) void cu_nodes_kernel(int B,
+                                                                const int32_t *__restrict__ n_kept,
+                                                                int32_t *__restrict__ cu_nodes) {
+  block_exclusive_scan(n_kept, cu_nodes, B);
+}
+
+// ------------------------------------------------------------------------------------
+// early head, bf16 MFMA
+// ------------------------------------------------------------------------------------
+// C[m][v] = sum_x A[m][x] * W[v][x].  Both operands are contiguous along x, which is
+// the layout the 32x32x16 MFMA wants (8 consecutive x per lane), so tiles go
+// global -> LDS -> registers without any transpose.  Workgroup tile 128 x 128,
+// K step 64, four waves in a 2 x 2 arrangement, each owning a 64 x 64 block
+// (2 x 2 MFMA tiles, 64 accumulator registers).  The next K step is fetched into
+// registers while the current one is multiplied.
+constexpr int kBM = 128, kBN = 128, kBK = 64, kPitch = kBK + 8;  // pitch 144 B: conflict-free b128
+constexpr int kGemmThreads = 256;
+
+__global__ __launch_bounds__(kGemmThreads) void early_head_bf16_kernel(
+    int hidden, int vocab, int B, const uint16_t *__restrict__ hidden_states,
+    const uint16_t *__restrict__ head_weight, const int32_t *__restrict__ row_src,
+    const int32_t *__restrict__ row_base, float *__restrict__ scores, size_t score_pitch) {
+  const int m_total = row_base[B];
+  const int m0 = blockIdx.x * kBM, v0 = blockIdx.y * kBN;
+  if (m0 >= m_total) return;
+
+  __shared__ __attribute__((aligned(16))) uint16_t As[kBM * kPitch];
+  __shared__ __attribute__((aligned(16))) uint16_t Bs[kBN * kPitch];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int l32 = lane & 31, g = lane >> 5;
+
+  // each thread moves four 16-byte chunks of A and of B per K step
+  const int ld_row = tid >> 3, ld_col = (tid & 7) * 8;
+  const uint16_t *a_ptr[4];
+  const uint16_t *b_ptr[4];
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int row = it * 32 + ld_row;
+    const int m = m0 + row, v = v0 + row;
+    a_ptr[it] = m < m_total ? hidden_states + (size_t)row_src[m] * hidden + ld_col : nullptr;
+    b_ptr[it] = v < vocab ? head_weight + (size_t)v * hidden + ld_col : nullptr;
+  }
+  const u32x4 zero4 = {0u, 0u, 0u, 0u};
+  u32x4 a_reg[4], b_reg[4];
+  auto fetch = [&](int k0) {
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      a_reg[it] = a_ptr[it] ? *reinterpret_cast<const u32x4 *>(a_ptr[it] + k0) : zero4;
+      b_reg[it] = b_ptr[it] ? *reinterpret_cast<const u32x4 *>(b_ptr[it] + k0) : zero4;
+    }
+  };
+  auto stash = [&]() {
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const int row = it * 32 + ld_row;
+      *reinterpret_cast<u32x4 *>(&As[row * kPitch + ld_col]) = a_reg[it];
+      *reinterpret_cast<u32x4 *>(&Bs[row * kPitch + ld_col]) = b_reg[it];
+    }
+  };
+
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int x = 0; x < 2; ++x)
+#pragma unroll
+    for (int y = 0; y < 2; ++y)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
+
+  fetch(0);
+  for (int k0 = 0; k0 < hidden; k0 += kBK) {
+    __syncthreads();  // previous step's reads are done
+    stash();
+    __syncthreads();
+    if (k0 + kBK < hidden) fetch(k0 + kBK);
+#pragma unroll
+    for (int ks = 0; ks < kBK / 16; ++ks) {
+      bf16x8 af[2], bf[2];
+#pragma unroll
+      for (int x = 0; x < 2; ++x) {
+        af[x] = *reinterpret_cast<const bf16x8 *>(
+            &As[(wm * 64 + x * 32 + l32) * kPitch + ks * 16 + g * 8]);
+        bf[x] = *reinterpret_cast<const bf16x8 *>(
+            &Bs[(wn * 64 + x * 32 + l32) * kPitch + ks * 16 + g * 8]);
+      }
+#pragma unroll
+      for (int x = 0; x < 2; ++x)
+#pragma unroll
+        for (int y = 0; y < 2; ++y)
+          acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[x], bf[y], acc[x][y], 0, 0, 0);
+    }
+  }
+
+  // accumulator layout of the 32x32 MFMA: lane -> column l32, register r -> row
+  // 8*(r/4) + 4*g + r%4
+#pragma unroll
+  for (int x = 0; x < 2; ++x)
+#pragma unroll
+    for (int y = 0; y < 2; ++y) {
+      const int col = v0 + wn * 64 + y * 32 + l32;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = m0 + wm * 64 + x * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+        if (row < m_total && col < vocab) scores[(size_t)row * score_pitch + col] = acc[x][y][r];
+      }
+    }
+}
+
+// fp32 variant: one score per thread, a plain sequential dot product.
+__global__ __launch_bounds__(256) void early_head_f32_kernel(
+    int hidden, int vocab, int B, const float *__restrict__ hidden_states,
+    const float *__restrict__ head_weight, const int32_t *__restrict__ row_src,
+    const int32_t *__restrict__ row_base, float *__restrict__ scores, size_t score_pitch) {
+  const int m = blockIdx.x;
+  if (m >= row_base[B]) return;
+  const int v = blockIdx.y * 256 + threadIdx.x;
+  if (v >= vocab) return;
+  const float *h = hidden_states + (size_t)row_src[m] * hidden;
+  const float *w = head_weight + (size_t)v * hidden;
+  float acc = 0.f;
+  for (int x = 0; x < hidden; ++x) acc = fmaf(h[x], w[x], acc);
+  scores[(size_t)m * score_pitch + v] = acc;
+}
+
+// ------------------------------------------------------------------------------------
+// top-k membership by counting
+// ------------------------------------------------------------------------------------
+constexpr int kRankThreads = 256;
+constexpr int kRankChunk = 8;
+
+__global__ __launch_bounds__(kRankThreads) void rank_count_kernel(
+    int B, int T_max, int vocab, const int32_t *__restrict__ n_nodes,
+    const int32_t *__restrict__ parent, const int32_t *__restrict__ token,
+    const int32_t *__restrict__ row_src, const int32_t *__restrict__ row_base,
+    const float *__restrict__ scores, size_t score_pitch, int32_t *__restrict__ rank) {
+  const int m = blockIdx.x;
+  if (m >= row_base[B]) return;
+  const int node = row_src[m];
+  const int b = node / T_max, p = node - b * T_max;
+  int T = n_nodes[b];
+  T = T < 1 ? 1 : (T > T_max ? T_max : T);
+  const int tid = threadIdx.x;
+  __shared__ int s_child[PROPD_MAX_TREE];
+  __shared__ int s_nchild;
+  __shared__ int s_count[kRankChunk];
+  if (tid == 0) s_nchild = 0;
+  __syncthreads();
+  if (tid > p && tid < T && parent[(size_t)b * T_max + tid] == p)
+    s_child[atomicAdd(&s_nchild, 1)] = tid;
+  __syncthreads();
+  const int nchild = s_nchild;
+  const float *z = scores + (size_t)m * score_pitch;
+  const int nvec = vocab >> 2;
+
+  for (int c0 = 0; c0 < nchild; c0 += kRankChunk) {
+    float thr[kRankChunk];
+    int tok[kRankChunk];
+    int cnt[kRankChunk];
+#pragma unroll
+    for (int e = 0; e < kRankChunk; ++e) {
+      thr[e] = INFINITY;  // unused slot: nothing beats +inf, nothing ties below id -1
+      tok[e] = -1;
+      cnt[e] = 0;
+      if (c0 + e < nchild) {
+        const int t = token[(size_t)b * T_max + s_child[c0 + e]];
+        if (t >= 0 && t < vocab) {
+          thr[e] = z[t];
+          tok[e] = t;
+        }
+      }
+    }
+    if (tid < kRankChunk) s_count[tid] = 0;
+    __syncthreads();
+    for (int c = tid; c < nvec; c += kRankThreads) {
+      const f32x4 u = *reinterpret_cast<const f32x4 *>(z + 4 * c);
+      const int v = 4 * c;
+#pragma unroll
+      for (int e = 0; e < kRankChunk; ++e) {
+        cnt[e] += (u.x > thr[e]) || (u.x == thr[e] && v < tok[e]);
+        cnt[e] += (u.y > thr[e]) || (u.y == thr[e] && v + 1 < tok[e]);
+        cnt[e] += (u.z > thr[e]) || (u.z == thr[e] && v + 2 < tok[e]);
+        cnt[e] += (u.w > thr[e]) || (u.w == thr[e] && v + 3 < tok[e]);
+      }
+    }
+    for (int v = 4 * nvec + tid; v < vocab; v += kRankThreads) {
+      const float x = z[v];
+#pragma unroll
+      for (int e = 0; e < kRankChunk; ++e) cnt[e] += (x > thr[e]) || (x == thr[e] && v < tok[e]);
+    }
+#pragma unroll
+    for (int e = 0; e < kRankChunk; ++e) {
+      const int s = wave_reduce_sum(cnt[e]);
+      if ((tid & 63) == 0 && s) atomicAdd(&s_count[e], s);
+    }
+    __syncthreads();
+    if (tid < kRankChunk && c0 + tid < nchild) {
+      // a token id outside the vocabulary can be in no top-k list
+      int mine = vocab;
+#pragma unroll
+      for (int e = 0; e < kRankChunk; ++e)
+        if (e == tid && tok[e] >= 0) mine = s_count[e];
+      rank[(size_t)b * T_max + s_child[c0 + tid]] = mine;
+    }
+    __syncthreads();
+  }
+}
+
+// ------------------------------------------------------------------------------------
+// branch elimination, compaction, mask subsampling
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(PROPD_MAX_TREE) void prune_compact_kernel(
+    int T_max, int top_k, const int32_t *__restrict__ n_nodes, const int32_t *__restrict__ parent,
+    const int32_t *__restrict__ token, const int32_t *__restrict__ depth,
+    const uint64_t *__restrict__ anc, const int32_t *__restrict__ rank,
+    uint64_t *__restrict__ keep_bits, int32_t *__restrict__ new_index,
+    int32_t *__restrict__ orig_index, int32_t *__restrict__ n_kept,
+    int32_t *__restrict__ out_n_nodes, int32_t *__restrict__ out_parent,
+    int32_t *__restrict__ out_token, int32_t *__restrict__ out_depth,
+    uint64_t *__restrict__ out_anc, int32_t *__restrict__ rank_out) {
+  const int b = blockIdx.x, i = threadIdx.x;
+  int T = n_nodes[b];
+  T = T < 1 ? 1 : (T > T_max ? T_max : T);
+  const size_t base = (size_t)b * T_max;
+  const bool valid = i < T;
+  __shared__ uint64_t s_fail[2], s_keep[2];
+
+  int my_rank = -1;
+  uint64_t a_lo = 0, a_hi = 0;
+  if (valid) {
+    my_rank = rank[base + i];
+    a_lo = anc[(base + i) * 2];
+    a_hi = anc[(base + i) * 2 + 1];
+  }
+  if (rank_out && i < T_max) rank_out[base + i] = my_rank;
+  const bool fail = valid && i > 0 && my_rank >= top_k;
+  const uint64_t fb = __ballot(fail);
+  if ((i & 63) == 0) s_fail[i >> 6] = fb;
+  __syncthreads();
+  // a node goes as soon as any node of its root path failed
+  const bool keep = valid && ((a_lo & s_fail[0]) | (a_hi & s_fail[1])) == 0;
+  const uint64_t kb = __ballot(keep);
+  if ((i & 63) == 0) s_keep[i >> 6] = kb;
+  __syncthreads();
+  const uint64_t k_lo = s_keep[0], k_hi = s_keep[1];
+  const int kept = __popcll(k_lo) + __popcll(k_hi);
+  const int ni = keep ? popc128_below(k_lo, k_hi, i) : -1;
+  if (i < T_max) new_index[base + i] = ni;
+  if (keep) {
+    orig_index[base + ni] = i;
+    out_token[base + ni] = token[base + i];
+    out_depth[base + ni] = depth[base + i];
+    int p = i == 0 ? -1 : parent[base + i];
+    out_parent[base + ni] = (p >= 0 && p < T) ? popc128_below(k_lo, k_hi, p) : -1;
+    // subsample the cached mask: keep the columns of survivors, renumbered
+    uint64_t r_lo = 0, r_hi = 0;
+    uint64_t w = a_lo & k_lo;
+    while (w) {
+      const int j = __ffsll((long long)w) - 1;
+      w &= w - 1;
+      const int pos = popc128_below(k_lo, k_hi, j);
+      if (pos < 64) r_lo |= 1ull << pos; else r_hi |= 1ull << (pos - 64);
+    }
+    w = a_hi & k_hi;
+    while (w) {
+      const int j = 64 + __ffsll((long long)w) - 1;
+      w &= w - 1;
+      const int pos = popc128_below(k_lo, k_hi, j);
+      if (pos < 64) r_lo |= 1ull << pos; else r_hi |= 1ull << (pos - 64);
+    }
+    out_anc[(base + ni) * 2] = r_lo;
+    out_anc[(base + ni) * 2 + 1] = r_hi;
+  }
+  if (i >= kept && i < T_max) {
+    orig_index[base + i] = -1;
+    out_token[base + i] = -1;
+    out_depth[base + i] = -1;
+    out_parent[base + i] = -1;
+    out_anc[(base + i) * 2] = 0;
+    out_anc[(base + i) * 2 + 1] = 0;
+  }
+  if (i == 0) {
+    keep_bits[2 * b] = k_lo;
+    keep_bits[2 * b + 1] = k_hi;
+    n_kept[b] = kept;
+    if (out_n_nodes) out_n_nodes[b] = kept;
+  }
+}
+
+// ------------------------------------------------------------------------------------
+// payload rows of survivors
+// ------------------------------------------------------------------------------------
+struct PayloadArgs {
+  const char *src[PROPD_MAX_PAYLOADS];
+  char *dst[PROPD_MAX_PAYLOADS];
+  unsigned long long row_bytes[PROPD_MAX_PAYLOADS];
+  long long outer[PROPD_MAX_PAYLOADS];
+  long long stride_b[PROPD_MAX_PAYLOADS], stride_outer[PROPD_MAX_PAYLOADS],
+      stride_t[PROPD_MAX_PAYLOADS];
+  int vec16[PROPD_MAX_PAYLOADS];  // rows, strides and bases are all 16-byte multiples
+};
+
+constexpr int kGatherThreads = 256;
+
+// One wave per destination row (b, o, j); blockIdx.y selects the payload.
+__global__ __launch_bounds__(kGatherThreads) void gather_rows_kernel(
+    PayloadArgs args, int B, int T_max, const int32_t *__restrict__ orig_index,
+    const int32_t *__restrict__ n_kept) {
+  const int pl = blockIdx.y;
+  const long long outer = args.outer[pl];
+  const long long rows = (long long)B * outer * T_max;
+  const long long row = (long long)blockIdx.x * (kGatherThreads / kWave) + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int j = (int)(row % T_max);
+  const long long bo = row / T_max;
+  const long long o = bo % outer;
+  const int b = (int)(bo / outer);
+  if (j >= n_kept[b]) return;
+  const int i = orig_index[(size_t)b * T_max + j];
+  if (i < 0 || i >= T_max) return;
+  const char *s = args.src[pl] + b * args.stride_b[pl] + o * args.stride_outer[pl] +
+                  (long long)i * args.stride_t[pl];
+  char *d = args.dst[pl] + b * args.stride_b[pl] + o * args.stride_outer[pl] +
+            (long long)j * args.stride_t[pl];
+  const unsigned long long nbytes = args.row_bytes[pl];
+  const int lane = threadIdx.x & 63;
+  if (args.vec16[pl]) {
+    const unsigned long long n16 = nbytes >> 4;
+    for (unsigned long long c = lane; c < n16; c += kWave)
+      reinterpret_cast<u32x4 *>(d)[c] = reinterpret_cast<const u32x4 *>(s)[c];
+  } else {
+    for (unsigned long long c = lane; c < nbytes; c += kWave) d[c] = s[c];
+  }
+}
+
+__global__ void fill_rank_kernel(int n, int T_max, const int32_t *__restrict__ n_nodes,
+                                 int32_t *__restrict__ rank) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= n) return;
+  const int b = idx / T_max, i = idx - b * T_max;
+  rank[idx] = i < n_nodes[b] ? 0 : -1;
+}
+
+}  // namespace propd
+
+extern "C" propd_status propd_early_prune(
+    const propd_tree *tree, propd_dtype dt, int32_t hidden, int32_t vocab, int32_t top_k,
+    const void *hidden_states, const void *head_weight, uint64_t *keep_bits, int32_t *new_index,
+    int32_t *orig_index, int32_t *n_kept, int32_t *cu_nodes, const propd_tree_out *tree_out,
+    int32_t *rank_out, int32_t n_payloads, const propd_payload *payloads, void *workspace,
+    size_t workspace_bytes, void *hip_stream) {
+  using namespace propd;
+  if (!tree || tree->B < 1 || tree->T_max < 1 || tree->T_max > PROPD_MAX_TREE || hidden < 1 ||
+      vocab < 1 || top_k < 1)
+    return PROPD_ERR_INVALID_ARG;
+  if (!tree->n_nodes || !tree->parent || !tree->token || !tree->depth || !tree->anc ||
+      !hidden_states || !head_weight || !keep_bits || !new_index || !orig_index || !n_kept ||
+      !cu_nodes || !tree_out || !tree_out->parent || !tree_out->token || !tree_out->depth ||
+      !tree_out->anc)
+    return PROPD_ERR_INVALID_ARG;
+  if (dt != PROPD_BF16 && dt != PROPD_F32) return PROPD_ERR_INVALID_ARG;
+  if (n_payloads < 0 || n_payloads > PROPD_MAX_PAYLOADS || (n_payloads > 0 && !payloads))
+    return PROPD_ERR_INVALID_ARG;
+  if (dt == PROPD_BF16 && hidden % kBK != 0) return PROPD_ERR_UNSUPPORTED;
+  const int B = tree->B, T_max = tree->T_max;
+  if ((long long)B * T_max > (1ll << 30)) return PROPD_ERR_UNSUPPORTED;
+  long long max_rows = 0;
+  PayloadArgs pa = {};
+  for (int p = 0; p < n_payloads; ++p) {
+    const propd_payload &pl = payloads[p];
+    if (!pl.src || !pl.dst || pl.outer < 1 || pl.row_bytes == 0 || pl.stride_t < 0 ||
+        pl.stride_b < 0 || pl.stride_outer < 0 || pl.src == pl.dst)
+      return PROPD_ERR_INVALID_ARG;
+    pa.src[p] = reinterpret_cast<const char *>(pl.src);
+    pa.dst[p] = reinterpret_cast<char *>(pl.dst);
+    pa.row_bytes[p] = pl.row_bytes;
+    pa.outer[p] = pl.outer;
+    pa.stride_b[p] = pl.stride_b;
+    pa.stride_outer[p] = pl.stride_outer;
+    pa.stride_t[p] = pl.stride_t;
+    const uintptr_t any = reinterpret_cast<uintptr_t>(pl.src) | reinterpret_cast<uintptr_t>(pl.dst) |
+                          (uintptr_t)pl.row_bytes | (uintptr_t)pl.stride_b |
+                          (uintptr_t)pl.stride_outer | (uintptr_t)pl.stride_t;
+    pa.vec16[p] = (any & 15) == 0;
+    const long long rows = (long long)B * pl.outer * T_max;
+    if (rows > (1ll << 31)) return PROPD_ERR_UNSUPPORTED;
+    max_rows = rows > max_rows ? rows : max_rows;
+  }
+  const size_t need = early_prune_workspace_bytes(B, T_max, vocab);
+  if (!workspace || workspace_bytes < need) return PROPD_ERR_WORKSPACE;
+  PruneScratch ws = carve_scratch(workspace, B, T_max, vocab);
+  hipStream_t st = as_stream(hip_stream);
+
+  if (top_k >= vocab) {
+    // every id is inside the list: nothing can fail, no scores are needed
+    const int n = B * T_max;
+    hipLaunchKernelGGL(fill_rank_kernel, dim3((n + 255) / 256), dim3(256), 0, st, n, T_max,
+                       tree->n_nodes, ws.rank);
+  } else {
+    hipLaunchKernelGGL(parent_rows_kernel, dim3(B), dim3(PROPD_MAX_TREE), 0, st, T_max,
+                       tree->n_nodes, tree->parent, ws.n_par, ws.local_list, ws.rank);
+    hipLaunchKernelGGL(row_table_kernel, dim3(1), dim3(kScanThreads), 0, st, B, T_max, ws.n_par,
+                       ws.local_list, ws.row_base, ws.row_src);
+    if (dt == PROPD_BF16) {
+      dim3 grid((unsigned)((ws.row_cap + kBM - 1) / kBM), (unsigned)((vocab + kBN - 1) / kBN));
+      hipLaunchKernelGGL(early_head_bf16_kernel, grid, dim3(kGemmThreads), 0, st, hidden, vocab, B,
+                         reinterpret_cast<const uint16_t *>(hidden_states),
+                         reinterpret_cast<const uint16_t *>(head_weight), ws.row_src, ws.row_base,
+                         ws.scores, ws.score_pitch);
+    } else {
+      dim3 grid((unsigned)ws.row_cap, (unsigned)((vocab + 255) / 256));
+      hipLaunchKernelGGL(early_head_f32_kernel, grid, dim3(256), 0, st, hidden, vocab, B,
+                         reinterpret_cast<const float *>(hidden_states),
+                         reinterpret_cast<const float *>(head_weight), ws.row_src, ws.row_base,
+                         ws.scores, ws.score_pitch);
+    }
+    hipLaunchKernelGGL(rank_count_kernel, dim3((unsigned)ws.row_cap), dim3(kRankThreads), 0, st, B,
+                       T_max, vocab, tree->n_nodes, tree->parent, tree->token, ws.row_src,
+                       ws.row_base, ws.scores, ws.score_pitch, ws.rank);
+  }
+  if (!launch_ok()) return PROPD_ERR_DEVICE;
+  hipLaunchKernelGGL(prune_compact_kernel, dim3(B), dim3(PROPD_MAX_TREE), 0, st, T_max, top_k,
+                     tree->n_nodes, tree->parent, tree->token, tree->depth, tree->anc, ws.rank,
+                     keep_bits, new_index, orig_index, n_kept, tree_out->n_nodes, tree_out->parent,
+                     tree_out->token, tree_out->depth, tree_out->anc, rank_out);
+  hipLaunchKernelGGL(cu_nodes_kernel, dim3(1), dim3(kScanThreads), 0, st, B, n_kept, cu_nodes);
+  if (n_payloads > 0) {
+    const unsigned per_block = kGatherThreads / kWave;
+    dim3 grid((unsigned)((max_rows + per_block - 1) / per_block), (unsigned)n_payloads);
+    hipLaunchKernelGGL(gather_rows_kernel, grid, dim3(kGatherThreads), 0, st, pa, B, T_max,
+                       orig_index, n_kept);
+  }
+  return launch_ok() ? PROPD_OK : PROPD_ERR_DEVICE;
+}

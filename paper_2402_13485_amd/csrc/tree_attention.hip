@@ -1,0 +1,528 @@
+// Tree-masked attention over the cached prefix plus each node's own root path
+// (Section 2, "Verification"; Figure 2(b,c)).
+//
+// bf16 path (d = 128).  The work is a stream of K/V rows from HBM that all T
+// tree queries of a (sequence, head) pair share, so the kernel is organised
+// around reading every K and V row exactly once:
+//   - one workgroup (4 waves) per (sequence, head, KV split); K/V tiles go
+//     global -> registers (prefetched one tile ahead) -> LDS, 16 bytes per lane,
+//     fully coalesced;
+//   - scores are computed transposed, S^T = K . Q^T, with the 32x32x16 bf16 MFMA,
+//     so that a lane owns one query column: the running max / sum of the online
+//     softmax are per-lane scalars, and the fp32 score registers, once
+//     exponentiated and rounded to bf16, ARE the B operand of the second MFMA
+//     O^T += V^T . P^T, with no shuffle or LDS round trip;
+//   - the cached prefix needs no mask; the tree part is one extra tile whose
+//     scores are kept only where the node's 128-bit ancestor set has the bit;
+//   - waves split the query columns (32 per wave) and, when the tree is small,
+//     also the rows of a tile; row groups are merged through LDS at the end;
+//   - a split writes an fp32 partial (O, max, sum); a second kernel merges
+//     splits.  With one split the result is written directly.
+// fp32 path: a plain one-wave-per-query kernel, fp32 throughout.
+#include "common.h"
+
+namespace propd {
+
+constexpr int kD = 128;
+constexpr int kAttnThreads = 256;
+constexpr int kKPitch = kD + 8;  // bf16 elements per K row in LDS (272 B)
+
+template <int TG>
+struct AttnCfg {
+  static constexpr int KG = 4 / TG;              // waves sharing one query group, splitting rows
+  static constexpr int NBW = (TG == 4) ? 2 : 1;  // 32-row blocks per wave per tile
+  static constexpr int TILE_J = 32 * KG * NBW;   // K/V rows per tile: 64, 64, 128
+  static constexpr int VPitch = TILE_J + 8;      // bf16 elements per V^T row in LDS
+  static constexpr int CH = TILE_J * 16 / kAttnThreads;  // 16-byte chunks per thread per tensor
+  static constexpr size_t tile_bytes = (size_t)(TILE_J * kKPitch + kD * VPitch) * 2;
+  static constexpr size_t merge_bytes = (size_t)(4 - TG) * 64 * 66 * 4;  // o[64] + m + l per lane
+  static constexpr size_t lds_bytes = tile_bytes > merge_bytes ? tile_bytes : merge_bytes;
+};
+
+struct AttnParams {
+  const uint16_t *q, *k_cache, *v_cache, *k_tree, *v_tree;
+  uint16_t *out;
+  const int32_t *seq_lens, *n_nodes;
+  const uint64_t *anc;
+  int H, T_max, L_max, n_split;
+  float scale_log2e;
+  float *part_o;   // [unit][split][128][128]
+  float *part_ml;  // [unit][split][128][2]
+};
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+template <int TG>
+__global__ __launch_bounds__(kAttnThreads) void tree_attn_bf16_kernel(AttnParams p) {
+  using C = AttnCfg<TG>;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  uint16_t *Ks = reinterpret_cast<uint16_t *>(smem);  // [TILE_J][kKPitch]
+  uint16_t *Vt = Ks + C::TILE_J * kKPitch;            // [kD][VPitch], V transposed
+
+  const int unit = blockIdx.x / p.n_split, split = blockIdx.x - unit * p.n_split;
+  const int b = unit / p.H;
+  int L = p.seq_lens[b];
+  L = L < 0 ? 0 : (L > p.L_max ? p.L_max : L);
+  int T = p.n_nodes[b];
+  T = T < 1 ? 1 : (T > p.T_max ? p.T_max : T);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, g = lane >> 5;
+  const int tg = wave % TG, kg = wave / TG;
+  const int t = tg * 32 + l32;  // this lane's query column
+
+  // tiles of this split: a slice of the cache, and on the last split the tree rows
+  const int n_cache_tiles = (L + C::TILE_J - 1) / C::TILE_J;
+  const int per_split = (n_cache_tiles + p.n_split - 1) / p.n_split;
+  const int tile_lo = split * per_split;
+  int n_cache_mine = n_cache_tiles - tile_lo;
+  n_cache_mine = n_cache_mine < 0 ? 0 : (n_cache_mine > per_split ? per_split : n_cache_mine);
+  const int n_tree_tiles = (split == p.n_split - 1) ? (T + C::TILE_J - 1) / C::TILE_J : 0;
+  const int n_tiles = n_cache_mine + n_tree_tiles;
+
+  const uint16_t *kc = p.k_cache + (size_t)unit * p.L_max * kD;
+  const uint16_t *vc = p.v_cache + (size_t)unit * p.L_max * kD;
+  const uint16_t *kt = p.k_tree + (size_t)unit * p.T_max * kD;
+  const uint16_t *vt = p.v_tree + (size_t)unit * p.T_max * kD;
+
+  // Q^T fragments: B operand, lane = query column, 8 consecutive d per K step
+  bf16x8 qf[8];
+  {
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+    const uint16_t *qrow = p.q + ((size_t)unit * p.T_max + (t < T ? t : 0)) * kD + g * 8;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      u32x4 v = t < T ? *reinterpret_cast<const u32x4 *>(qrow + ks * 16) : zero4;
+      qf[ks] = __builtin_bit_cast(bf16x8, v);
+    }
+  }
+  uint64_t anc_lo = 0, anc_hi = 0;
+  if (t < T) {
+    anc_lo = p.anc[((size_t)b * p.T_max + t) * 2];
+    anc_hi = p.anc[((size_t)b * p.T_max + t) * 2 + 1];
+  }
+
+  float m_run = -INFINITY, l_run = 0.f;
+  f32x16 o_acc[4];
+#pragma unroll
+  for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o_acc[mb][r] = 0.f;
+
+  // ---- tile fetch: 16-byte chunks, chunk c -> row c/16, columns (c%16)*8 .. +8
+  u32x4 k_reg[C::CH], v_reg[C::CH];
+  auto fetch = [&](int it) {
+    const bool is_tree = it >= n_cache_mine;
+    const int j0 = is_tree ? (it - n_cache_mine) * C::TILE_J : (tile_lo + it) * C::TILE_J;
+    const int rows_valid = (is_tree ? T : L) - j0;
+    const uint16_t *ksrc = (is_tree ? kt : kc) + (size_t)j0 * kD;
+    const uint16_t *vsrc = (is_tree ? vt : vc) + (size_t)j0 * kD;
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int i = 0; i < C::CH; ++i) {
+      const int c = i * kAttnThreads + tid;
+      const int row = c >> 4;
+      const bool ok = row < rows_valid;  // rows beyond the valid ones read as zero
+      k_reg[i] = ok ? *reinterpret_cast<const u32x4 *>(ksrc + (size_t)c * 8) : zero4;
+      v_reg[i] = ok ? *reinterpret_cast<const u32x4 *>(vsrc + (size_t)c * 8) : zero4;
+    }
+  };
+  auto stash = [&]() {
+#pragma unroll
+    for (int i = 0; i < C::CH; ++i) {
+      const int c = i * kAttnThreads + tid;
+      const int row = c >> 4, col = (c & 15) * 8;
+      *reinterpret_cast<u32x4 *>(&Ks[row * kKPitch + col]) = k_reg[i];
+      const uint32_t w[4] = {v_reg[i].x, v_reg[i].y, v_reg[i].z, v_reg[i].w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        Vt[(col + 2 * e) * C::VPitch + row] = (uint16_t)(w[e] & 0xffffu);
+        Vt[(col + 2 * e + 1) * C::VPitch + row] = (uint16_t)(w[e] >> 16);
+      }
+    }
+  };
+
+  if (n_tiles > 0) fetch(0);
+  for (int it = 0; it < n_tiles; ++it) {
+    __syncthreads();  // the previous tile has been consumed
+    stash();
+    __syncthreads();
+    if (it + 1 < n_tiles) fetch(it + 1);
+
+    const bool is_tree = it >= n_cache_mine;
+    const int j0 = is_tree ? (it - n_cache_mine) * C::TILE_J : (tile_lo + it) * C::TILE_J;
+    const int limit = is_tree ? T : L;
+
+    // ---- S^T = K . Q^T for this wave's row blocks
+    f32x16 s[C::NBW];
+#pragma unroll
+    for (int nb = 0; nb < C::NBW; ++nb) {
+      const int jb = kg * C::NBW + nb;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[nb][r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        const bf16x8 a =
+            *reinterpret_cast<const bf16x8 *>(&Ks[(jb * 32 + l32) * kKPitch + ks * 16 + g * 8]);
+        s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[nb], 0, 0, 0);
+      }
+    }
+    // ---- scale, mask, running max.  Register r of a 32x32 accumulator holds row
+    //      8*(r/4) + 4*g + r%4 of the block, i.e. K/V row j of the tile.
+    float m_blk = -INFINITY;
+#pragma unroll
+    for (int nb = 0; nb < C::NBW; ++nb) {
+      const int jb = kg * C::NBW + nb;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int j = j0 + jb * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+        bool ok = j < limit;
+        if (is_tree) ok = ok && test_bit128(anc_lo, anc_hi, j);
+        const float x = ok ? s[nb][r] * p.scale_log2e : -INFINITY;
+        s[nb][r] = x;
+        m_blk = fmaxf(m_blk, x);
+      }
+    }
+    m_blk = fmaxf(m_blk, __shfl_xor(m_blk, 32, kWave));
+    const float m_new = fmaxf(m_run, m_blk);
+    const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+    const float alpha = fast_exp2(m_run - m_safe);
+    m_run = m_new;
+    l_run *= alpha;
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o_acc[mb][r] *= alpha;
+
+    // ---- P^T (bf16) straight from the score registers, then O^T += V^T . P^T
+#pragma unroll
+    for (int nb = 0; nb < C::NBW; ++nb) {
+      const int jb = kg * C::NBW + nb;
+      float pr[16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        pr[r] = fast_exp2(s[nb][r] - m_safe);
+        l_run += pr[r];
+      }
+#pragma unroll
+      for (int ks2 = 0; ks2 < 2; ++ks2) {
+        u32x4 pw;
+        pw.x = pack_bf16x2(pr[8 * ks2 + 0], pr[8 * ks2 + 1]);
+        pw.y = pack_bf16x2(pr[8 * ks2 + 2], pr[8 * ks2 + 3]);
+        pw.z = pack_bf16x2(pr[8 * ks2 + 4], pr[8 * ks2 + 5]);
+        pw.w = pack_bf16x2(pr[8 * ks2 + 6], pr[8 * ks2 + 7]);
+        const bf16x8 pf = __builtin_bit_cast(bf16x8, pw);
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb) {
+          // A operand: lane = d index, slots 0..3 rows 16*ks2+4g.., slots 4..7 rows +8
+          const uint16_t *vrow = &Vt[(mb * 32 + l32) * C::VPitch + jb * 32 + 16 * ks2 + 4 * g];
+          const u32x2 lo = *reinterpret_cast<const u32x2 *>(vrow);
+          const u32x2 hi = *reinterpret_cast<const u32x2 *>(vrow + 8);
+          const u32x4 aw = {lo.x, lo.y, hi.x, hi.y};
+          o_acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, aw), pf,
+                                                              o_acc[mb], 0, 0, 0);
+        }
+      }
+    }
+  }
+
+  // ---- merge the row groups of one query group through LDS (lane-wise)
+  l_run += __shfl_xor(l_run, 32, kWave);
+  if (C::KG > 1) {
+    float *mg = reinterpret_cast<float *>(smem);
+    __syncthreads();
+    if (kg > 0) {
+      float *slot = mg + (size_t)((kg - 1) * TG + tg) * 66 * 64;
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) slot[(mb * 16 + r) * 64 + lane] = o_acc[mb][r];
+      slot[64 * 64 + lane] = m_run;
+      slot[65 * 64 + lane] = l_run;
+    }
+    __syncthreads();
+    if (kg == 0) {
+#pragma unroll
+      for (int k2 = 1; k2 < C::KG; ++k2) {
+        const float *slot = mg + (size_t)((k2 - 1) * TG + tg) * 66 * 64;
+        const float m2 = slot[64 * 64 + lane], l2 = slot[65 * 64 + lane];
+        const float m_new = fmaxf(m_run, m2);
+        const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+        const float a1 = fast_exp2(m_run - m_safe), a2 = fast_exp2(m2 - m_safe);
+        l_run = l_run * a1 + l2 * a2;
+        m_run = m_new;
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            o_acc[mb][r] = o_acc[mb][r] * a1 + slot[(mb * 16 + r) * 64 + lane] * a2;
+      }
+    }
+  }
+  if (kg != 0 || t >= T) return;
+
+  // ---- write: lane holds d = mb*32 + 8*(r/4) + 4*g + r%4 for its query t
+  if (p.n_split == 1) {
+    const float inv = 1.f / l_run;
+    uint16_t *orow = p.out + ((size_t)unit * p.T_max + t) * kD;
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        u32x2 w;
+        w.x = pack_bf16x2(o_acc[mb][4 * q4] * inv, o_acc[mb][4 * q4 + 1] * inv);
+        w.y = pack_bf16x2(o_acc[mb][4 * q4 + 2] * inv, o_acc[mb][4 * q4 + 3] * inv);
+        *reinterpret_cast<u32x2 *>(orow + mb * 32 + 8 * q4 + 4 * g) = w;
+      }
+  } else {
+    const size_t slot = (size_t)unit * p.n_split + split;
+    float *po = p.part_o + (slot * 128 + t) * kD;
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const f32x4 w = {o_acc[mb][4 * q4], o_acc[mb][4 * q4 + 1], o_acc[mb][4 * q4 + 2],
+                         o_acc[mb][4 * q4 + 3]};
+        *reinterpret_cast<f32x4 *>(po + mb * 32 + 8 * q4 + 4 * g) = w;
+      }
+    if (g == 0) {
+      p.part_ml[(slot * 128 + t) * 2] = m_run;
+      p.part_ml[(slot * 128 + t) * 2 + 1] = l_run;
+    }
+  }
+}
+
+// Merge the splits of one (sequence, head): out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
+__global__ __launch_bounds__(kAttnThreads) void tree_attn_combine_kernel(AttnParams p) {
+  const int unit = blockIdx.x;
+  const int b = unit / p.H;
+  int T = p.n_nodes[b];
+  T = T < 1 ? 1 : (T > p.T_max ? p.T_max : T);
+  for (int item = threadIdx.x; item < T * (kD / 4); item += kAttnThreads) {
+    const int t = item / (kD / 4), d4 = (item - t * (kD / 4)) * 4;
+    float M = -INFINITY;
+    for (int s = 0; s < p.n_split; ++s)
+      M = fmaxf(M, p.part_ml[(((size_t)unit * p.n_split + s) * 128 + t) * 2]);
+    if (M == -INFINITY) M = 0.f;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    float lsum = 0.f;
+    for (int s = 0; s < p.n_split; ++s) {
+      const size_t slot = (size_t)unit * p.n_split + s;
+      const float w = fast_exp2(p.part_ml[(slot * 128 + t) * 2] - M);
+      lsum += w * p.part_ml[(slot * 128 + t) * 2 + 1];
+      if (w != 0.f) {
+        const f32x4 o = *reinterpret_cast<const f32x4 *>(p.part_o + (slot * 128 + t) * kD + d4);
+        acc += o * w;
+      }
+    }
+    const float inv = 1.f / lsum;
+    u32x2 w2;
+    w2.x = pack_bf16x2(acc.x * inv, acc.y * inv);
+    w2.y = pack_bf16x2(acc.z * inv, acc.w * inv);
+    *reinterpret_cast<u32x2 *>(p.out + ((size_t)unit * p.T_max + t) * kD + d4) = w2;
+  }
+}
+
+// ------------------------------------------------------------------------------------
+// fp32 path: one wave per (sequence, head, node); fp32 loads, products, softmax, output.
+// ------------------------------------------------------------------------------------
+struct AttnParamsF32 {
+  const float *q, *k_cache, *v_cache, *k_tree, *v_tree;
+  float *out;
+  const int32_t *seq_lens, *n_nodes;
+  const uint64_t *anc;
+  int H, T_max, L_max, d;
+  float scale;
+};
+
+__global__ __launch_bounds__(kWave) void tree_attn_f32_kernel(AttnParamsF32 p) {
+  const int unit = blockIdx.x / p.T_max, i = blockIdx.x - unit * p.T_max;
+  const int b = unit / p.H;
+  int L = p.seq_lens[b];
+  L = L < 0 ? 0 : (L > p.L_max ? p.L_max : L);
+  int T = p.n_nodes[b];
+  T = T < 1 ? 1 : (T > p.T_max ? p.T_max : T);
+  if (i >= T) return;
+  const int lane = threadIdx.x, d = p.d;
+  const uint64_t a_lo = p.anc[((size_t)b * p.T_max + i) * 2];
+  const uint64_t a_hi = p.anc[((size_t)b * p.T_max + i) * 2 + 1];
+  const float *q = p.q + ((size_t)unit * p.T_max + i) * d;
+  const float *kc = p.k_cache + (size_t)unit * p.L_max * d;
+  const float *vc = p.v_cache + (size_t)unit * p.L_max * d;
+  const float *kt = p.k_tree + (size_t)unit * p.T_max * d;
+  const float *vt = p.v_tree + (size_t)unit * p.T_max * d;
+
+  float m_run = -INFINITY, l_run = 0.f, o0 = 0.f, o1 = 0.f;  // lane owns columns lane, lane+64
+  const int total = L + T;
+  for (int j0 = 0; j0 < total; j0 += kWave) {
+    const int j = j0 + lane;
+    const bool in_cache = j < L;
+    const int jt = j - L;
+    const bool ok = in_cache || (j < total && test_bit128(a_lo, a_hi, jt));
+    float s = -INFINITY;
+    if (ok) {
+      const float *kr = in_cache ? kc + (size_t)j * d : kt + (size_t)jt * d;
+      float acc = 0.f;
+      for (int x = 0; x < d; ++x) acc = fmaf(q[x], kr[x], acc);
+      s = acc * p.scale;
+    }
+    const float m_new = fmaxf(m_run, wave_reduce_max(s));
+    if (m_new == -INFINITY) continue;  // nothing visible in this chunk (uniform across the wave)
+    const float alpha = expf(m_run - m_new);
+    const float w = ok ? expf(s - m_new) : 0.f;
+    l_run = l_run * alpha + wave_reduce_sum(w);
+    o0 *= alpha;
+    o1 *= alpha;
+    m_run = m_new;
+    const uint64_t live = __ballot(w != 0.f);
+    for (uint64_t rest = live; rest; rest &= rest - 1) {
+      const int src = __ffsll((long long)rest) - 1;
+      const float wj = __shfl(w, src, kWave);
+      const int jj = j0 + src;
+      const float *vr = jj < L ? vc + (size_t)jj * d : vt + (size_t)(jj - L) * d;
+      if (lane < d) o0 = fmaf(wj, vr[lane], o0);
+      if (lane + 64 < d) o1 = fmaf(wj, vr[lane + 64], o1);
+    }
+  }
+  float *o = p.out + ((size_t)unit * p.T_max + i) * d;
+  if (lane < d) o[lane] = o0 / l_run;
+  if (lane + 64 < d) o[lane + 64] = o1 / l_run;
+}
+
+// ------------------------------------------------------------------------------------
+// host side
+// ------------------------------------------------------------------------------------
+static int pick_tg(int T_max) { return T_max <= 32 ? 1 : (T_max <= 64 ? 2 : 4); }
+
+static int tile_rows(int tg) { return tg == 1 ? AttnCfg<1>::TILE_J : AttnCfg<4>::TILE_J; }
+
+// KV splits: enough workgroups to cover the chip a few times over, but never
+// fewer than two tiles per split.
+static int pick_splits(int B, int H, int L_max, int T_max) {
+  const long long units = (long long)B * H;
+  const int tile = tile_rows(pick_tg(T_max));
+  const int max_by_len = L_max / (2 * tile) > 1 ? L_max / (2 * tile) : 1;
+  long long want = (1024 + units - 1) / units;
+  if (want < 1) want = 1;
+  if (want > max_by_len) want = max_by_len;
+  if (want > 64) want = 64;
+  return (int)want;
+}
+
+size_t tree_attention_workspace_bytes(int B, int H, int L_max, int T_max) {
+  const int ns = pick_splits(B, H, L_max, T_max);
+  if (ns == 1) return 256;
+  const size_t slots = (size_t)B * H * ns;
+  return align_up(slots * 128 * kD * 4, 256) + align_up(slots * 128 * 2 * 4, 256);
+}
+
+template <int TG>
+static bool launch_bf16(const AttnParams &p, int units, hipStream_t st) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_attn_bf16_kernel<TG>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)AttnCfg<TG>::lds_bytes) != hipSuccess)
+      return false;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(tree_attn_bf16_kernel<TG>, dim3((unsigned)(units * p.n_split)),
+                     dim3(kAttnThreads), AttnCfg<TG>::lds_bytes, st, p);
+  return launch_ok();
+}
+
+}  // namespace propd
+
+extern "C" propd_status propd_tree_attention(const propd_tree *tree, propd_dtype dt, int32_t H,
+                                             int32_t d, float scale, const void *q,
+                                             const void *k_cache, const void *v_cache,
+                                             const void *k_tree, const void *v_tree,
+                                             const int32_t *seq_lens, int32_t L_max, void *out,
+                                             void *workspace, size_t workspace_bytes,
+                                             void *hip_stream) {
+  using namespace propd;
+  if (!tree || tree->B < 1 || tree->T_max < 1 || tree->T_max > PROPD_MAX_TREE || H < 1 ||
+      L_max < 0 || !tree->n_nodes || !tree->anc || !q || !k_tree || !v_tree || !seq_lens || !out ||
+      (L_max > 0 && (!k_cache || !v_cache)))
+    return PROPD_ERR_INVALID_ARG;
+  if (dt != PROPD_BF16 && dt != PROPD_F32) return PROPD_ERR_INVALID_ARG;
+  const long long units = (long long)tree->B * H;
+  if (units * tree->T_max > (1ll << 30)) return PROPD_ERR_UNSUPPORTED;
+  hipStream_t st = as_stream(hip_stream);
+
+  if (dt == PROPD_F32) {
+    if (d != 64 && d != 128) return PROPD_ERR_UNSUPPORTED;
+    AttnParamsF32 p;
+    p.q = reinterpret_cast<const float *>(q);
+    p.k_cache = reinterpret_cast<const float *>(k_cache);
+    p.v_cache = reinterpret_cast<const float *>(v_cache);
+    p.k_tree = reinterpret_cast<const float *>(k_tree);
+    p.v_tree = reinterpret_cast<const float *>(v_tree);
+    p.out = reinterpret_cast<float *>(out);
+    p.seq_lens = seq_lens;
+    p.n_nodes = tree->n_nodes;
+    p.anc = tree->anc;
+    p.H = H;
+    p.T_max = tree->T_max;
+    p.L_max = L_max;
+    p.d = d;
+    p.scale = scale;
+    hipLaunchKernelGGL(tree_attn_f32_kernel, dim3((unsigned)(units * tree->T_max)), dim3(kWave), 0,
+                       st, p);
+    return launch_ok() ? PROPD_OK : PROPD_ERR_DEVICE;
+  }
+
+  if (d != kD) return PROPD_ERR_UNSUPPORTED;
+  const size_t need = tree_attention_workspace_bytes(tree->B, H, L_max, tree->T_max);
+  if (!workspace || workspace_bytes < need) return PROPD_ERR_WORKSPACE;
+  AttnParams p;
+  p.q = reinterpret_cast<const uint16_t *>(q);
+  p.k_cache = reinterpret_cast<const uint16_t *>(k_cache);
+  p.v_cache = reinterpret_cast<const uint16_t *>(v_cache);
+  p.k_tree = reinterpret_cast<const uint16_t *>(k_tree);
+  p.v_tree = reinterpret_cast<const uint16_t *>(v_tree);
+  p.out = reinterpret_cast<uint16_t *>(out);
+  p.seq_lens = seq_lens;
+  p.n_nodes = tree->n_nodes;
+  p.anc = tree->anc;
+  p.H = H;
+  p.T_max = tree->T_max;
+  p.L_max = L_max;
+  p.n_split = pick_splits(tree->B, H, L_max, tree->T_max);
+  p.scale_log2e = scale * 1.4426950408889634f;
+  const size_t slots = (size_t)units * p.n_split;
+  p.part_o = reinterpret_cast<float *>(workspace);
+  p.part_ml = reinterpret_cast<float *>(reinterpret_cast<char *>(workspace) +
+                                        align_up(slots * 128 * kD * 4, 256));
+  bool ok;
+  switch (pick_tg(tree->T_max)) {
+    case 1: ok = launch_bf16<1>(p, (int)units, st); break;
+    case 2: ok = launch_bf16<2>(p, (int)units, st); break;
+    default: ok = launch_bf16<4>(p, (int)units, st); break;
+  }
+  if (!ok) return PROPD_ERR_DEVICE;
+  if (p.n_split > 1) {
+    hipLaunchKernelGGL(tree_attn_combine_kernel, dim3((unsigned)units), dim3(kAttnThreads), 0, st,
+                       p);
+    if (!launch_ok()) return PROPD_ERR_DEVICE;
+  }
+  return PROPD_OK;
+}
+
+extern "C" size_t propd_workspace_bytes(propd_ws_kind which, int32_t B, int32_t T_max, int32_t H,
+                                        int32_t d, int32_t L_max, int32_t hidden, int32_t vocab) {
+  (void)d;
+  (void)hidden;
+  if (B < 1 || T_max < 1 || T_max > PROPD_MAX_TREE) return 0;
+  switch (which) {
+    case PROPD_WS_TREE_ATTENTION:
+      if (H < 1 || L_max < 0) return 0;
+      return propd::tree_attention_workspace_bytes(B, H, L_max, T_max);
+    case PROPD_WS_EARLY_PRUNE:
+      if (vocab < 1) return 0;
+      return propd::early_prune_workspace_bytes(B, T_max, vocab);
+    case PROPD_WS_ACCEPT_PATH:
+      return propd::align_up((size_t)B * T_max * 4, 256);
+  }
+  return 0;
+}

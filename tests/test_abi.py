@@ -1,0 +1,100 @@
+"""The shared library loads without a GPU, exports every entry point the header
+declares, and rejects bad scalars on the host before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "propd.h")
+
+
+@pytest.fixture(scope="module")
+def pb():
+    from paper_2402_13485_amd import binding, build
+    if not os.path.exists(binding.LIB_PATH):
+        build.build()
+    return binding
+
+
+def declared_entry_points():
+    text = open(HEADER).read()
+    return re.findall(r"PROPD_API\s+[\w\s\*]+?\b(propd_\w+)\s*\(", text)
+
+
+def test_header_declares_the_expected_calls():
+    names = declared_entry_points()
+    for n in ("propd_tree_attention", "propd_early_prune", "propd_accept_path", "propd_tree_mask",
+              "propd_workspace_bytes", "propd_status_string"):
+        assert n in names
+
+
+def test_library_exports_every_declared_symbol(pb):
+    lib = pb.load_library()
+    for name in declared_entry_points():
+        assert hasattr(lib, name), name
+    assert set(declared_entry_points()) == set(pb.EXPORTS)
+
+
+def test_status_strings(pb):
+    lib = pb.load_library()
+    seen = {lib.propd_status_string(c) for c in range(5)}
+    assert len(seen) == 5 and all(s for s in seen)
+
+
+def test_workspace_sizes(pb):
+    assert pb.workspace_bytes(pb.WS_TREE_ATTENTION, 16, 128, 40, 128, 4096) > 0
+    big = pb.workspace_bytes(pb.WS_EARLY_PRUNE, 16, 128, hidden=5120, vocab=32000)
+    assert big >= 16 * 127 * 32000 * 4  # fp32 scores for every node that can have children
+    assert pb.workspace_bytes(pb.WS_ACCEPT_PATH, 16, 128, vocab=32000) >= 16 * 128 * 4
+    assert pb.workspace_bytes(pb.WS_ACCEPT_PATH, 16, 129, vocab=32000) == 0  # tree too large
+    assert pb.workspace_bytes(7, 16, 128) == 0
+
+
+def test_bad_scalars_are_rejected_on_the_host(pb):
+    lib = pb.load_library()
+    INVALID, UNSUPPORTED, WORKSPACE = 1, 2, 3
+    fake = ctypes.c_void_p(0x1000)  # never dereferenced: validation fails first
+    assert lib.propd_tree_mask(0, 16, fake, fake, fake, fake, None) == INVALID
+    assert lib.propd_tree_mask(1, 129, fake, fake, fake, fake, None) == INVALID
+    assert lib.propd_tree_mask(1, 16, None, fake, fake, fake, None) == INVALID
+    tree = pb._Tree(1, 16, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000)
+    t = ctypes.byref(tree)
+    # attention: bad dtype, unsupported head size, missing workspace
+    args = (fake, fake, fake, fake, fake, fake, 128, fake)
+    assert lib.propd_tree_attention(t, 5, 1, 128, 1.0, *args, fake, 1 << 30, None) == INVALID
+    assert lib.propd_tree_attention(t, pb.PROPD_BF16, 1, 96, 1.0, *args, fake, 1 << 30, None) \
+        == UNSUPPORTED
+    assert lib.propd_tree_attention(t, pb.PROPD_F32, 1, 80, 1.0, *args, fake, 1 << 30, None) \
+        == UNSUPPORTED
+    assert lib.propd_tree_attention(t, pb.PROPD_BF16, 1, 128, 1.0, *args, None, 0, None) \
+        == WORKSPACE
+    assert lib.propd_tree_attention(t, pb.PROPD_BF16, 0, 128, 1.0, *args, fake, 1 << 30, None) \
+        == INVALID
+    # early prune: top_k < 1, hidden not a multiple of 64 for bf16, short workspace
+    tout = pb._TreeOut(0x1000, 0x1000, 0x1000, 0x1000, 0x1000)
+    o = ctypes.byref(tout)
+    outs = (fake, fake, fake, fake, fake)
+    assert lib.propd_early_prune(t, pb.PROPD_BF16, 128, 1000, 0, fake, fake, *outs, o, None, 0,
+                                 None, fake, 1 << 30, None) == INVALID
+    assert lib.propd_early_prune(t, pb.PROPD_BF16, 100, 1000, 4, fake, fake, *outs, o, None, 0,
+                                 None, fake, 1 << 30, None) == UNSUPPORTED
+    assert lib.propd_early_prune(t, pb.PROPD_BF16, 128, 1000, 4, fake, fake, *outs, o, None, 0,
+                                 None, fake, 16, None) == WORKSPACE
+    assert lib.propd_early_prune(t, pb.PROPD_BF16, 128, 1000, 4, fake, fake, *outs, o, None, 9,
+                                 None, fake, 1 << 30, None) == INVALID
+    # accept: vocabulary and stride must be positive
+    assert lib.propd_accept_path(t, pb.PROPD_BF16, 0, fake, fake, fake, 8, fake, fake, 1 << 20,
+                                 None) == INVALID
+    assert lib.propd_accept_path(t, pb.PROPD_BF16, 100, fake, fake, fake, 0, fake, fake, 1 << 20,
+                                 None) == INVALID
+    assert lib.propd_accept_path(t, pb.PROPD_BF16, 100, fake, fake, fake, 8, fake, None, 0,
+                                 None) == WORKSPACE
+
+
+def test_binding_has_no_fallback(pb, monkeypatch):
+    monkeypatch.setattr(pb, "_lib", None)
+    monkeypatch.setattr(pb, "LIB_PATH", os.path.join(ROOT, "does_not_exist.so"))
+    with pytest.raises(RuntimeError):
+        pb.load_library()
