@@ -64,6 +64,18 @@ __device__ __forceinline__ bool test_bit128(uint64_t lo, uint64_t hi, int j) {
   return ((j < 64 ? (lo >> j) : (hi >> (j - 64))) & 1ull) != 0;
 }
 
+// Results of an MFMA chain are read by vector ALU code right after it.  Observed on
+// gfx950 with this toolchain: when a branch sits between the last MFMA and the first
+// read, the reads can be issued before the matrix core has written the registers
+// back (stale accumulator values, no error).  An explicit wait covering the longest
+// MFMA used here (8 passes of 4 cycles) closes the window; the scheduling barriers
+// keep the compiler from moving either side across it.
+__device__ __forceinline__ void mfma_settle() {
+  __builtin_amdgcn_sched_barrier(0);
+  asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 7" ::: "memory");
+  __builtin_amdgcn_sched_barrier(0);
+}
+
 inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }

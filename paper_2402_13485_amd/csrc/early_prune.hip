@@ -225,6 +225,7 @@ __global__ __launch_bounds__(kGemmThreads) void early_head_bf16_kernel(
     }
   }
 
+  mfma_settle();
   // accumulator layout of the 32x32 MFMA: lane -> column l32, register r -> row
   // 8*(r/4) + 4*g + r%4
 #pragma unroll

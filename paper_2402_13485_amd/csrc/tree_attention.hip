@@ -149,9 +149,21 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_bf16_kernel(AttnParams
     __syncthreads();
     if (it + 1 < n_tiles) fetch(it + 1);
 
+    // Tile-local validity mask of this lane's query: cached rows below L are visible to
+    // every query, tree rows only where the ancestor set has the bit.  Built without
+    // branches so that the MFMA chain below and the code consuming it stay in one block.
     const bool is_tree = it >= n_cache_mine;
     const int j0 = is_tree ? (it - n_cache_mine) * C::TILE_J : (tile_lo + it) * C::TILE_J;
-    const int limit = is_tree ? T : L;
+    int n_valid = (is_tree ? T : L) - j0;
+    n_valid = n_valid < 0 ? 0 : (n_valid > C::TILE_J ? C::TILE_J : n_valid);
+    uint64_t vis_lo, vis_hi;
+    mask_below(n_valid, vis_lo, vis_hi);
+    {
+      const uint64_t t_lo = j0 >= 64 ? anc_hi : anc_lo;  // tree tiles start at row 0 or 64
+      const uint64_t t_hi = j0 >= 64 ? 0ull : anc_hi;
+      vis_lo &= is_tree ? t_lo : ~0ull;
+      vis_hi &= is_tree ? t_hi : ~0ull;
+    }
 
     // ---- S^T = K . Q^T for this wave's row blocks
     f32x16 s[C::NBW];
@@ -167,17 +179,18 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_bf16_kernel(AttnParams
         s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[nb], 0, 0, 0);
       }
     }
+    mfma_settle();
     // ---- scale, mask, running max.  Register r of a 32x32 accumulator holds row
     //      8*(r/4) + 4*g + r%4 of the block, i.e. K/V row j of the tile.
     float m_blk = -INFINITY;
 #pragma unroll
     for (int nb = 0; nb < C::NBW; ++nb) {
       const int jb = kg * C::NBW + nb;
+      const uint64_t word = (jb & 2) ? vis_hi : vis_lo;
+      const uint32_t vis = (uint32_t)(word >> ((jb & 1) * 32)) >> (4 * g);
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int j = j0 + jb * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-        bool ok = j < limit;
-        if (is_tree) ok = ok && test_bit128(anc_lo, anc_hi, j);
+        const bool ok = (vis >> (8 * (r >> 2) + (r & 3))) & 1u;
         const float x = ok ? s[nb][r] * p.scale_log2e : -INFINITY;
         s[nb][r] = x;
         m_blk = fmaxf(m_blk, x);
@@ -227,6 +240,7 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_bf16_kernel(AttnParams
   }
 
   // ---- merge the row groups of one query group through LDS (lane-wise)
+  mfma_settle();
   l_run += __shfl_xor(l_run, 32, kWave);
   if (C::KG > 1) {
     float *mg = reinterpret_cast<float *>(smem);

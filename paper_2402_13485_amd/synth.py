@@ -308,11 +308,15 @@ def plant_accept_chain(rng: np.random.Generator, logits: np.ndarray, n_nodes: np
                 row[token[b, chain[a + 1]]] = top
             else:
                 used = {int(token[b, c]) for c in kids_of[node]}
-                while True:
-                    v = int(rng.integers(0, V))
-                    if v not in used:
-                        break
-                row[v] = top
+                free = [v for v in range(V) if v not in used] if len(used) * 2 >= V else None
+                if free is None:
+                    while True:
+                        v = int(rng.integers(0, V))
+                        if v not in used:
+                            break
+                    row[v] = top
+                elif free:
+                    row[free[int(rng.integers(0, len(free)))]] = top
         chains.append(chain)
     return chains
 
