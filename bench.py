@@ -1,0 +1,243 @@
+#!/usr/bin/env python3
+"""Benchmark of the token-tree verification step on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch of seeded synthetic
+input, in the order the method runs it (Section 4.1, Figure 5):
+    tree attention on the full tree        (a layer before the pruning point)
+    early prune: head scores, top-k test, branch elimination, compaction of the
+                 tree, the mask and the row payloads (hidden, q, tree K/V)
+    tree attention on the compacted tree   (a layer after the pruning point)
+    greedy acceptance on the compacted tree
+Inputs are resident in HBM before the timed region starts.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 4] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, vendor figure
+
+
+def log(msg: str) -> None:
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def build_inputs(w, synth):
+    """Host-side seeded inputs of one workload ('Synthetic inputs')."""
+    t0 = time.time()
+    seq_lens = synth.workload_seq_lens(w)
+    trees = synth.workload_trees(w)
+    att = synth.make_attention_inputs(w, seq_lens=seq_lens, trees=trees, poison=True)
+    log(f"attention tensors generated in {time.time() - t0:.1f}s")
+    t0 = time.time()
+    if w.top_k > 0:
+        pr = synth.make_prune_inputs(w, trees=trees)
+        token = pr["token"]
+    else:
+        pr = None
+        token = synth.draw_tokens(synth.rng_for(w.index, 3), att["n_nodes"], att["parent"], w.vocab)
+    log(f"early-head tensors and token placement in {time.time() - t0:.1f}s")
+    t0 = time.time()
+    acc = synth.make_accept_inputs(w, att["n_nodes"], att["parent"], token)
+    log(f"final logits in {time.time() - t0:.1f}s")
+    return att, pr, acc, token
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", type=int, default=4, choices=[2, 3, 4, 5])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; nothing here uses a second one "
+              "(sequences and heads shard with no exchange, see DESIGN.md). Use --gpus 1.",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2402_13485_amd import binding as pb
+    from paper_2402_13485_amd import synth
+    to_dev, to_host = pb.to_device, pb.to_host
+
+    pb.load_library()  # fails loudly if the HIP library is not built
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    w = synth.WORKLOADS[args.workload]
+    att, pr, acc, token = build_inputs(w, synth)
+    B, H, d, T_max, L_max = att["B"], att["H"], att["d"], att["T_max"], att["L_max"]
+
+    # ---- upload; everything below stays resident
+    t0 = time.time()
+    nn, par = to_dev(att["n_nodes"]), to_dev(att["parent"])
+    depth, anc = pb.propd_tree_mask(nn, par)
+    tree = pb.Tree(n_nodes=nn, parent=par, token=to_dev(token), depth=depth, anc=anc)
+    q, kc, vc = to_dev(att["q"]), to_dev(att["k_cache"]), to_dev(att["v_cache"])
+    kt, vt = to_dev(att["k_tree"]), to_dev(att["v_tree"])
+    seq = to_dev(att["seq_lens"])
+    out_full = torch.empty_like(q)
+    out_small = torch.empty_like(q)
+    ws_att = torch.empty(max(256, pb.workspace_bytes(pb.WS_TREE_ATTENTION, B, T_max, H, d, L_max)),
+                         dtype=torch.uint8, device="cuda")
+    ws_acc = torch.empty(pb.workspace_bytes(pb.WS_ACCEPT_PATH, B, T_max, vocab=w.vocab),
+                         dtype=torch.uint8, device="cuda")
+    prune = w.top_k > 0
+    if prune:
+        hid, hw = to_dev(pr["hidden_states"]), to_dev(pr["head_weight"])
+        ws_pr = torch.empty(pb.workspace_bytes(pb.WS_EARLY_PRUNE, B, T_max, hidden=w.hidden,
+                                               vocab=w.vocab), dtype=torch.uint8, device="cuda")
+        payloads = [hid, q, kt, vt]
+        payload_out = [torch.zeros_like(x) for x in payloads]
+    logits_full = to_dev(acc["logits"])
+    torch.cuda.synchronize()
+    log(f"upload {time.time() - t0:.1f}s")
+
+    # final-layer logits of the compacted tree are an INPUT of the acceptance step: prepare
+    # them once, untimed, by narrowing the synthetic full-tree logits to the survivors
+    if prune:
+        res0 = pb.propd_early_prune(tree, hid, hw, w.top_k, payloads=[logits_full], workspace=ws_pr)
+        logits_small = res0.payloads[0]
+        torch.cuda.synchronize()
+        n_kept_host = to_host(res0.n_kept)
+    else:
+        logits_small = logits_full
+        n_kept_host = att["n_nodes"]
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def step(marks=None):
+        """One pass of the hot path; `marks` collects events around the parts."""
+        m = [ev() for _ in range(5)] if marks is not None else None
+        if m: m[0].record()
+        pb.propd_tree_attention(tree, q, kc, vc, kt, vt, seq, att["scale"], out=out_full,
+                                workspace=ws_att)
+        if m: m[1].record()
+        if prune:
+            res = pb.propd_early_prune(tree, hid, hw, w.top_k, payloads=payloads,
+                                       payload_out=payload_out, workspace=ws_pr)
+            if m: m[2].record()
+            pb.propd_tree_attention(res.tree, payload_out[1], kc, vc, payload_out[2],
+                                    payload_out[3], seq, att["scale"], out=out_small,
+                                    workspace=ws_att)
+            t_acc = res.tree
+        else:
+            if m: m[2].record()
+            t_acc = tree
+        if m: m[3].record()
+        r = pb.propd_accept_path(t_acc, logits_small, path_stride=8, workspace=ws_acc)
+        if m: m[4].record()
+        if marks is not None:
+            marks.append(m)
+        return r
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    marks = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        last = step(marks)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+
+    parts = np.array([[m[i].elapsed_time(m[i + 1]) for i in range(4)] for m in marks])  # ms
+    att_full_ms, prune_ms, att_small_ms, accept_ms = parts.mean(axis=0)
+    sum_T = int(att["n_nodes"].sum())
+    kv_bytes = float(sum(int(L) for L in att["seq_lens"])) * H * d * 2 * 2
+    side_bytes = float(sum_T) * H * d * 2 * 4  # q, k_tree, v_tree read; out written
+    alg_bytes = kv_bytes + side_bytes
+    achieved = alg_bytes / (att_full_ms * 1e-3) / 1e9
+    accept_len = to_host(last[0])
+
+    result = {
+        "metric": "verified tree tokens/s (B*T)",
+        "value": sum_T / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "B": B, "H": H, "d": d, "L_max": L_max, "T_max": T_max,
+                   "sum_L": int(att["seq_lens"].sum()), "sum_T": sum_T, "hidden": w.hidden,
+                   "vocab": w.vocab, "top_k": w.top_k,
+                   "survivors": int(np.sum(n_kept_host)),
+                   "mean_accept_len": float(accept_len.mean())},
+        "parts_us": {"attention_full_tree": att_full_ms * 1e3, "early_prune": prune_ms * 1e3,
+                     "attention_compacted_tree": att_small_ms * 1e3, "accept": accept_ms * 1e3},
+        "roofline": {"kernel": "tree_attn_bf16_kernel (full tree) + combine", "bound": "hbm",
+                     "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "algorithmic_bytes": alg_bytes,
+                     "kv_stream_gbps": kv_bytes / (att_full_ms * 1e-3) / 1e9,
+                     "kv_stream_frac": kv_bytes / (att_full_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                     "compacted_tree_kv_gbps": kv_bytes / (att_small_ms * 1e-3) / 1e9
+                     if prune else None},
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, att, pr, acc, token)
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+def cpu_baseline(w, att, pr, acc, token):
+    """The oracle, as it stands, timed on this host on a bounded sample of the workload:
+    the first `Bs` sequences through the same four parts.  A reported baseline only."""
+    from oracle import oracle
+    oracle.build()
+    Bs = w.B
+    Hs = att["H"]
+    sl = slice(0, Bs)
+    hs = slice(0, Hs)
+    cut = lambda a: np.ascontiguousarray(a[sl][:, hs])
+    n_nodes, parent, seq = att["n_nodes"][sl], att["parent"][sl], att["seq_lens"][sl]
+    q, kc, vc, kt, vt = (cut(att[k]) for k in ("q", "k_cache", "v_cache", "k_tree", "v_tree"))
+    t0 = time.perf_counter()
+    oracle.tree_attention(n_nodes, parent, seq, q, kc, vc, kt, vt, att["scale"])
+    t_att = time.perf_counter() - t0
+    t_pr = t_att2 = 0.0
+    tree2 = (n_nodes, parent, token[sl])
+    logits = acc["logits"][sl]
+    if pr is not None:
+        t0 = time.perf_counter()
+        rank, _ = oracle.early_head_rank(n_nodes, parent, token[sl], pr["hidden_states"][sl],
+                                         pr["head_weight"], w.top_k)
+        c = oracle.prune_compact(n_nodes, parent, token[sl], rank, w.top_k)
+        g = lambda a: oracle.gather_rows(a, c["orig_index"], c["n_kept"])
+        q2, kt2, vt2 = g(q), g(kt), g(vt)
+        g(pr["hidden_states"][sl])
+        t_pr = time.perf_counter() - t0
+        logits = g(logits)
+        t0 = time.perf_counter()
+        oracle.tree_attention(c["n_kept"], c["parent"], seq, q2, kc, vc, kt2, vt2, att["scale"])
+        t_att2 = time.perf_counter() - t0
+        tree2 = (c["n_kept"], c["parent"], c["token"])
+    t0 = time.perf_counter()
+    oracle.accept_path(tree2[0], tree2[1], tree2[2], logits)
+    t_acc = time.perf_counter() - t0
+    total = t_att + t_att2 + t_pr + t_acc
+    return {"value": float(n_nodes.sum()) / total, "unit": "tokens/s", "cores": oracle.threads(),
+            "kind": "oracle",
+            "sample": f"{Bs} of {w.B} sequences, all heads, through the same four parts "
+                      f"({int(n_nodes.sum())} tree tokens)",
+            "seconds": {"attention_full_tree": t_att, "early_prune": t_pr,
+                        "attention_compacted_tree": t_att2, "accept": t_acc, "total": total}}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

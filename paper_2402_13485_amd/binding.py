@@ -12,6 +12,7 @@ import os
 from dataclasses import dataclass
 from typing import Optional, Sequence
 
+import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -75,6 +76,23 @@ def load_library() -> ctypes.CDLL:
     lib.propd_status_string.argtypes = [ctypes.c_int]
     _lib = lib
     return lib
+
+
+def to_device(a: "np.ndarray") -> torch.Tensor:
+    """numpy -> GPU tensor.  uint16 arrays are bf16 bit patterns; uint64 travels as int64."""
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+    if a.dtype == np.uint64:
+        return torch.from_numpy(a.view(np.int64)).cuda()
+    return torch.from_numpy(a).cuda()
+
+
+def to_host(t: torch.Tensor) -> "np.ndarray":
+    """GPU tensor -> numpy; bf16 comes back as uint16 bit patterns."""
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
 
 
 class PropdError(RuntimeError):

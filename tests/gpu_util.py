@@ -5,21 +5,7 @@ import torch
 from paper_2402_13485_amd import synth
 
 
-def to_dev(a: np.ndarray) -> torch.Tensor:
-    """numpy -> cuda tensor; uint16 arrays are bf16 bit patterns, uint64 travel as int64."""
-    a = np.ascontiguousarray(a)
-    if a.dtype == np.uint16:
-        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
-    if a.dtype == np.uint64:
-        return torch.from_numpy(a.view(np.int64)).cuda()
-    return torch.from_numpy(a).cuda()
-
-
-def to_host(t: torch.Tensor) -> np.ndarray:
-    """cuda tensor -> numpy; bf16 comes back as uint16 bit patterns."""
-    if t.dtype == torch.bfloat16:
-        return t.view(torch.int16).cpu().numpy().view(np.uint16)
-    return t.cpu().numpy()
+from paper_2402_13485_amd.binding import to_device as to_dev, to_host  # noqa: E402,F401
 
 
 def host_f64(t: torch.Tensor) -> np.ndarray:
