@@ -25,16 +25,19 @@ namespace propd {
 
 constexpr int kD = 128;
 constexpr int kAttnThreads = 256;
-constexpr int kKPitch = kD + 8;  // bf16 elements per K row in LDS (272 B)
+constexpr int kKPitch = kD + 8;   // bf16 elements per K row in LDS: 272 B, conflict-free b128 reads
+constexpr int kVPitch = kD + 32;  // bf16 elements per V row in LDS: 320 B, conflict-free transpose reads
 
 template <int TG>
 struct AttnCfg {
   static constexpr int KG = 4 / TG;              // waves sharing one query group, splitting rows
   static constexpr int NBW = (TG == 4) ? 2 : 1;  // 32-row blocks per wave per tile
   static constexpr int TILE_J = 32 * KG * NBW;   // K/V rows per tile: 64, 64, 128
-  static constexpr int VPitch = TILE_J + 8;      // bf16 elements per V^T row in LDS
   static constexpr int CH = TILE_J * 16 / kAttnThreads;  // 16-byte chunks per thread per tensor
-  static constexpr size_t tile_bytes = (size_t)(TILE_J * kKPitch + kD * VPitch) * 2;
+  static constexpr int k_elems = TILE_J * kKPitch;
+  static constexpr int v_elems = TILE_J * kVPitch;
+  static constexpr size_t buf_bytes = (size_t)(k_elems + v_elems) * 2;
+  static constexpr size_t tile_bytes = 2 * buf_bytes;  // double buffered
   static constexpr size_t merge_bytes = (size_t)(4 - TG) * 64 * 66 * 4;  // o[64] + m + l per lane
   static constexpr size_t lds_bytes = tile_bytes > merge_bytes ? tile_bytes : merge_bytes;
 };
@@ -44,295 +47,386 @@ struct AttnParams {
   uint16_t *out;
   const int32_t *seq_lens, *n_nodes;
   const uint64_t *anc;
-  int H, T_max, L_max, n_split;
+  int B, H, T_max, L_max;
   float scale_log2e;
-  float *part_o;   // [unit][split][128][128]
-  float *part_ml;  // [unit][split][128][2]
+  float *part_o;   // [2 * grid][128][128]
+  float *part_ml;  // [2 * grid][128][2]
 };
+
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __attribute__((ext_vector_type(4))) short s16x4;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// two floats -> packed bf16 pair (round to nearest even), one v_cvt_pk_bf16_f32
+__device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
+  const f32x2 f = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+}
+
+// Work decomposition shared by the main kernel and the merge kernel.  The work of one
+// call is the list of K/V tiles of all (sequence, head) units in order, each unit's
+// cached tiles followed by its tree tiles.  Workgroup w of G owns the contiguous range
+// [w*N/G, (w+1)*N/G) of that list, so every workgroup streams the same number of rows
+// whatever the mix of sequence lengths; a unit cut by a range boundary is finished by
+// the merge kernel from per-workgroup partial results.
+template <int TILE_J>
+struct TileMap {
+  int B, H;
+  const int32_t *seq_lens, *n_nodes;
+  int L_max, T_max;
+  __device__ __forceinline__ int len(int b) const {
+    const int L = seq_lens[b];
+    return L < 0 ? 0 : (L > L_max ? L_max : L);
+  }
+  __device__ __forceinline__ int nodes(int b) const {
+    const int T = n_nodes[b];
+    return T < 1 ? 1 : (T > T_max ? T_max : T);
+  }
+  __device__ __forceinline__ int cache_tiles(int b) const { return (len(b) + TILE_J - 1) / TILE_J; }
+  __device__ __forceinline__ int tree_tiles(int b) const { return (nodes(b) + TILE_J - 1) / TILE_J; }
+  __device__ __forceinline__ int unit_tiles(int b) const { return cache_tiles(b) + tree_tiles(b); }
+  __device__ long long total() const {
+    long long n = 0;
+    for (int b = 0; b < B; ++b) n += (long long)H * unit_tiles(b);
+    return n;
+  }
+};
+
+__device__ __forceinline__ long long range_start(long long w, long long n, long long g) {
+  return w * n / g;
+}
+
 template <int TG>
-__global__ __launch_bounds__(kAttnThreads) void tree_attn_bf16_kernel(AttnParams p) {
+__global__ __launch_bounds__(kAttnThreads, TG == 1 ? 1 : 2) void tree_attn_bf16_kernel(AttnParams p) {
   using C = AttnCfg<TG>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  uint16_t *Ks = reinterpret_cast<uint16_t *>(smem);  // [TILE_J][kKPitch]
-  uint16_t *Vt = Ks + C::TILE_J * kKPitch;            // [kD][VPitch], V transposed
-
-  const int unit = blockIdx.x / p.n_split, split = blockIdx.x - unit * p.n_split;
-  const int b = unit / p.H;
-  int L = p.seq_lens[b];
-  L = L < 0 ? 0 : (L > p.L_max ? p.L_max : L);
-  int T = p.n_nodes[b];
-  T = T < 1 ? 1 : (T > p.T_max ? p.T_max : T);
+  uint16_t *lds = reinterpret_cast<uint16_t *>(smem);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, g = lane >> 5;
   const int tg = wave % TG, kg = wave / TG;
   const int t = tg * 32 + l32;  // this lane's query column
 
-  // tiles of this split: a slice of the cache, and on the last split the tree rows
-  const int n_cache_tiles = (L + C::TILE_J - 1) / C::TILE_J;
-  const int per_split = (n_cache_tiles + p.n_split - 1) / p.n_split;
-  const int tile_lo = split * per_split;
-  int n_cache_mine = n_cache_tiles - tile_lo;
-  n_cache_mine = n_cache_mine < 0 ? 0 : (n_cache_mine > per_split ? per_split : n_cache_mine);
-  const int n_tree_tiles = (split == p.n_split - 1) ? (T + C::TILE_J - 1) / C::TILE_J : 0;
-  const int n_tiles = n_cache_mine + n_tree_tiles;
+  const TileMap<C::TILE_J> map = {p.B, p.H, p.seq_lens, p.n_nodes, p.L_max, p.T_max};
+  const long long n_total = map.total();
+  const long long G = gridDim.x, w = blockIdx.x;
+  long long x = range_start(w, n_total, G);
+  const long long x_end = range_start(w + 1, n_total, G);
 
-  const uint16_t *kc = p.k_cache + (size_t)unit * p.L_max * kD;
-  const uint16_t *vc = p.v_cache + (size_t)unit * p.L_max * kD;
-  const uint16_t *kt = p.k_tree + (size_t)unit * p.T_max * kD;
-  const uint16_t *vt = p.v_tree + (size_t)unit * p.T_max * kD;
-
-  // Q^T fragments: B operand, lane = query column, 8 consecutive d per K step
-  bf16x8 qf[8];
-  {
-    const u32x4 zero4 = {0u, 0u, 0u, 0u};
-    const uint16_t *qrow = p.q + ((size_t)unit * p.T_max + (t < T ? t : 0)) * kD + g * 8;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      u32x4 v = t < T ? *reinterpret_cast<const u32x4 *>(qrow + ks * 16) : zero4;
-      qf[ks] = __builtin_bit_cast(bf16x8, v);
+  int b = 0;
+  long long b_start = 0;  // first tile of sequence b in the global list
+  while (x < x_end) {
+    // ---- locate the unit that owns tile x (x only grows, so b only grows)
+    while (b < p.B - 1 && x >= b_start + (long long)p.H * map.unit_tiles(b)) {
+      b_start += (long long)p.H * map.unit_tiles(b);
+      ++b;
     }
-  }
-  uint64_t anc_lo = 0, anc_hi = 0;
-  if (t < T) {
-    anc_lo = p.anc[((size_t)b * p.T_max + t) * 2];
-    anc_hi = p.anc[((size_t)b * p.T_max + t) * 2 + 1];
-  }
+    const int L = map.len(b), T = map.nodes(b);
+    const int ut = map.unit_tiles(b), n_cache_tiles = map.cache_tiles(b);
+    const int h = (int)((x - b_start) / ut);
+    const int tile0 = (int)((x - b_start) - (long long)h * ut);
+    const long long unit_end = b_start + (long long)(h + 1) * ut;
+    const int n_tiles = (int)((unit_end < x_end ? unit_end : x_end) - x);
+    const bool whole = tile0 == 0 && n_tiles == ut;
+    const int unit = b * p.H + h;
 
-  float m_run = -INFINITY, l_run = 0.f;
-  f32x16 o_acc[4];
-#pragma unroll
-  for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) o_acc[mb][r] = 0.f;
+    const uint16_t *kc = p.k_cache + (size_t)unit * p.L_max * kD;
+    const uint16_t *vc = p.v_cache + (size_t)unit * p.L_max * kD;
+    const uint16_t *kt = p.k_tree + (size_t)unit * p.T_max * kD;
+    const uint16_t *vt = p.v_tree + (size_t)unit * p.T_max * kD;
 
-  // ---- tile fetch: 16-byte chunks, chunk c -> row c/16, columns (c%16)*8 .. +8
-  u32x4 k_reg[C::CH], v_reg[C::CH];
-  auto fetch = [&](int it) {
-    const bool is_tree = it >= n_cache_mine;
-    const int j0 = is_tree ? (it - n_cache_mine) * C::TILE_J : (tile_lo + it) * C::TILE_J;
-    const int rows_valid = (is_tree ? T : L) - j0;
-    const uint16_t *ksrc = (is_tree ? kt : kc) + (size_t)j0 * kD;
-    const uint16_t *vsrc = (is_tree ? vt : vc) + (size_t)j0 * kD;
-    const u32x4 zero4 = {0u, 0u, 0u, 0u};
-#pragma unroll
-    for (int i = 0; i < C::CH; ++i) {
-      const int c = i * kAttnThreads + tid;
-      const int row = c >> 4;
-      const bool ok = row < rows_valid;  // rows beyond the valid ones read as zero
-      k_reg[i] = ok ? *reinterpret_cast<const u32x4 *>(ksrc + (size_t)c * 8) : zero4;
-      v_reg[i] = ok ? *reinterpret_cast<const u32x4 *>(vsrc + (size_t)c * 8) : zero4;
-    }
-  };
-  auto stash = [&]() {
-#pragma unroll
-    for (int i = 0; i < C::CH; ++i) {
-      const int c = i * kAttnThreads + tid;
-      const int row = c >> 4, col = (c & 15) * 8;
-      *reinterpret_cast<u32x4 *>(&Ks[row * kKPitch + col]) = k_reg[i];
-      const uint32_t w[4] = {v_reg[i].x, v_reg[i].y, v_reg[i].z, v_reg[i].w};
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        Vt[(col + 2 * e) * C::VPitch + row] = (uint16_t)(w[e] & 0xffffu);
-        Vt[(col + 2 * e + 1) * C::VPitch + row] = (uint16_t)(w[e] >> 16);
-      }
-    }
-  };
-
-  if (n_tiles > 0) fetch(0);
-  for (int it = 0; it < n_tiles; ++it) {
-    __syncthreads();  // the previous tile has been consumed
-    stash();
-    __syncthreads();
-    if (it + 1 < n_tiles) fetch(it + 1);
-
-    // Tile-local validity mask of this lane's query: cached rows below L are visible to
-    // every query, tree rows only where the ancestor set has the bit.  Built without
-    // branches so that the MFMA chain below and the code consuming it stay in one block.
-    const bool is_tree = it >= n_cache_mine;
-    const int j0 = is_tree ? (it - n_cache_mine) * C::TILE_J : (tile_lo + it) * C::TILE_J;
-    int n_valid = (is_tree ? T : L) - j0;
-    n_valid = n_valid < 0 ? 0 : (n_valid > C::TILE_J ? C::TILE_J : n_valid);
-    uint64_t vis_lo, vis_hi;
-    mask_below(n_valid, vis_lo, vis_hi);
+    // Q^T fragments: B operand, lane = query column, 8 consecutive d per K step
+    bf16x8 qf[8];
     {
-      const uint64_t t_lo = j0 >= 64 ? anc_hi : anc_lo;  // tree tiles start at row 0 or 64
-      const uint64_t t_hi = j0 >= 64 ? 0ull : anc_hi;
-      vis_lo &= is_tree ? t_lo : ~0ull;
-      vis_hi &= is_tree ? t_hi : ~0ull;
-    }
-
-    // ---- S^T = K . Q^T for this wave's row blocks
-    f32x16 s[C::NBW];
-#pragma unroll
-    for (int nb = 0; nb < C::NBW; ++nb) {
-      const int jb = kg * C::NBW + nb;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) s[nb][r] = 0.f;
+      const u32x4 zero4 = {0u, 0u, 0u, 0u};
+      const uint16_t *qrow = p.q + ((size_t)unit * p.T_max + (t < T ? t : 0)) * kD + g * 8;
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 a =
-            *reinterpret_cast<const bf16x8 *>(&Ks[(jb * 32 + l32) * kKPitch + ks * 16 + g * 8]);
-        s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[nb], 0, 0, 0);
+        u32x4 v = t < T ? *reinterpret_cast<const u32x4 *>(qrow + ks * 16) : zero4;
+        qf[ks] = __builtin_bit_cast(bf16x8, v);
       }
     }
-    mfma_settle();
-    // ---- scale, mask, running max.  Register r of a 32x32 accumulator holds row
-    //      8*(r/4) + 4*g + r%4 of the block, i.e. K/V row j of the tile.
-    float m_blk = -INFINITY;
-#pragma unroll
-    for (int nb = 0; nb < C::NBW; ++nb) {
-      const int jb = kg * C::NBW + nb;
-      const uint64_t word = (jb & 2) ? vis_hi : vis_lo;
-      const uint32_t vis = (uint32_t)(word >> ((jb & 1) * 32)) >> (4 * g);
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const bool ok = (vis >> (8 * (r >> 2) + (r & 3))) & 1u;
-        const float x = ok ? s[nb][r] * p.scale_log2e : -INFINITY;
-        s[nb][r] = x;
-        m_blk = fmaxf(m_blk, x);
-      }
+    uint64_t anc_lo = 0, anc_hi = 0;
+    if (t < T) {
+      anc_lo = p.anc[((size_t)b * p.T_max + t) * 2];
+      anc_hi = p.anc[((size_t)b * p.T_max + t) * 2 + 1];
     }
-    m_blk = fmaxf(m_blk, __shfl_xor(m_blk, 32, kWave));
-    const float m_new = fmaxf(m_run, m_blk);
-    const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-    const float alpha = fast_exp2(m_run - m_safe);
-    m_run = m_new;
-    l_run *= alpha;
+
+    float m_run = -INFINITY, l_run = 0.f;
+    f32x16 o_acc[4];
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) o_acc[mb][r] *= alpha;
+      for (int r = 0; r < 16; ++r) o_acc[mb][r] = 0.f;
 
-    // ---- P^T (bf16) straight from the score registers, then O^T += V^T . P^T
+    // ---- tile fetch: 16-byte chunks, chunk c -> row c/16, columns (c%16)*8 .. +8
+    u32x4 k_reg[C::CH], v_reg[C::CH];
+    auto fetch = [&](int it) {
+      const int tile = tile0 + it;
+      const bool is_tree = tile >= n_cache_tiles;
+      const int j0 = (is_tree ? tile - n_cache_tiles : tile) * C::TILE_J;
+      const int rows_valid = (is_tree ? T : L) - j0;
+      const uint16_t *ksrc = (is_tree ? kt : kc) + (size_t)j0 * kD;
+      const uint16_t *vsrc = (is_tree ? vt : vc) + (size_t)j0 * kD;
+      const u32x4 zero4 = {0u, 0u, 0u, 0u};
 #pragma unroll
-    for (int nb = 0; nb < C::NBW; ++nb) {
-      const int jb = kg * C::NBW + nb;
-      float pr[16];
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        pr[r] = fast_exp2(s[nb][r] - m_safe);
-        l_run += pr[r];
+      for (int i = 0; i < C::CH; ++i) {
+        const int c = i * kAttnThreads + tid;
+        const bool ok = (c >> 4) < rows_valid;  // rows beyond the valid ones read as zero
+        k_reg[i] = ok ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(ksrc) + c) : zero4;
+        v_reg[i] = ok ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(vsrc) + c) : zero4;
       }
+    };
+    auto stash = [&](int buf) {
+      uint16_t *Ks = lds + buf * (C::k_elems + C::v_elems);
+      uint16_t *Vs = Ks + C::k_elems;
 #pragma unroll
-      for (int ks2 = 0; ks2 < 2; ++ks2) {
-        u32x4 pw;
-        pw.x = pack_bf16x2(pr[8 * ks2 + 0], pr[8 * ks2 + 1]);
-        pw.y = pack_bf16x2(pr[8 * ks2 + 2], pr[8 * ks2 + 3]);
-        pw.z = pack_bf16x2(pr[8 * ks2 + 4], pr[8 * ks2 + 5]);
-        pw.w = pack_bf16x2(pr[8 * ks2 + 6], pr[8 * ks2 + 7]);
-        const bf16x8 pf = __builtin_bit_cast(bf16x8, pw);
+      for (int i = 0; i < C::CH; ++i) {
+        const int c = i * kAttnThreads + tid;
+        const int row = c >> 4, col = (c & 15) * 8;
+        *reinterpret_cast<u32x4 *>(&Ks[row * kKPitch + col]) = k_reg[i];
+        *reinterpret_cast<u32x4 *>(&Vs[row * kVPitch + col]) = v_reg[i];
+      }
+    };
+
+    fetch(0);
+    stash(0);
+    if (n_tiles > 1) fetch(1);
+    __syncthreads();
+
+    for (int it = 0; it < n_tiles; ++it) {
+      const int cur = it & 1;
+      // tile it+1 is in registers: park it in the other buffer (free since the last
+      // barrier), then start loading tile it+2; both overlap with the math below
+      if (it + 1 < n_tiles) stash(cur ^ 1);
+      if (it + 2 < n_tiles) fetch(it + 2);
+
+      const uint16_t *Ks = lds + cur * (C::k_elems + C::v_elems);
+      const uint16_t *Vs = Ks + C::k_elems;
+      const int tile = tile0 + it;
+      const bool is_tree = tile >= n_cache_tiles;
+      const int j0 = (is_tree ? tile - n_cache_tiles : tile) * C::TILE_J;
+      int n_valid = (is_tree ? T : L) - j0;
+      n_valid = n_valid > C::TILE_J ? C::TILE_J : n_valid;
+      const bool partial = is_tree || n_valid < C::TILE_J;  // uniform over the workgroup
+
+      // ---- S^T = K . Q^T for this wave's row blocks
+      f32x16 s[C::NBW];
 #pragma unroll
-        for (int mb = 0; mb < 4; ++mb) {
-          // A operand: lane = d index, slots 0..3 rows 16*ks2+4g.., slots 4..7 rows +8
-          const uint16_t *vrow = &Vt[(mb * 32 + l32) * C::VPitch + jb * 32 + 16 * ks2 + 4 * g];
-          const u32x2 lo = *reinterpret_cast<const u32x2 *>(vrow);
-          const u32x2 hi = *reinterpret_cast<const u32x2 *>(vrow + 8);
-          const u32x4 aw = {lo.x, lo.y, hi.x, hi.y};
-          o_acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, aw), pf,
-                                                              o_acc[mb], 0, 0, 0);
+      for (int nb = 0; nb < C::NBW; ++nb) {
+        const int jb = kg * C::NBW + nb;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[nb][r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+          const bf16x8 a =
+              *reinterpret_cast<const bf16x8 *>(&Ks[(jb * 32 + l32) * kKPitch + ks * 16 + g * 8]);
+          s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[nb], 0, 0, 0);
         }
       }
-    }
-  }
+      mfma_settle();
 
-  // ---- merge the row groups of one query group through LDS (lane-wise)
-  mfma_settle();
-  l_run += __shfl_xor(l_run, 32, kWave);
-  if (C::KG > 1) {
-    float *mg = reinterpret_cast<float *>(smem);
-    __syncthreads();
-    if (kg > 0) {
-      float *slot = mg + (size_t)((kg - 1) * TG + tg) * 66 * 64;
+      // ---- scale (log2 domain), mask, running max.  Register r of a 32x32 accumulator
+      //      holds row 8*(r/4) + 4*g + r%4 of the block, i.e. K/V row j of the tile.
 #pragma unroll
-      for (int mb = 0; mb < 4; ++mb)
+      for (int nb = 0; nb < C::NBW; ++nb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) slot[(mb * 16 + r) * 64 + lane] = o_acc[mb][r];
-      slot[64 * 64 + lane] = m_run;
-      slot[65 * 64 + lane] = l_run;
-    }
-    __syncthreads();
-    if (kg == 0) {
+        for (int r = 0; r < 16; ++r) s[nb][r] *= p.scale_log2e;
+      if (partial) {
+        // tile-local visibility of this lane's query: cached rows below L for every
+        // query, tree rows only where the node's ancestor set has the bit
+        uint64_t vis_lo, vis_hi;
+        mask_below(n_valid, vis_lo, vis_hi);
+        const uint64_t t_lo = j0 >= 64 ? anc_hi : anc_lo;  // tree tiles start at row 0 or 64
+        const uint64_t t_hi = j0 >= 64 ? 0ull : anc_hi;
+        vis_lo &= is_tree ? t_lo : ~0ull;
+        vis_hi &= is_tree ? t_hi : ~0ull;
 #pragma unroll
-      for (int k2 = 1; k2 < C::KG; ++k2) {
-        const float *slot = mg + (size_t)((k2 - 1) * TG + tg) * 66 * 64;
-        const float m2 = slot[64 * 64 + lane], l2 = slot[65 * 64 + lane];
-        const float m_new = fmaxf(m_run, m2);
-        const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-        const float a1 = fast_exp2(m_run - m_safe), a2 = fast_exp2(m2 - m_safe);
-        l_run = l_run * a1 + l2 * a2;
-        m_run = m_new;
+        for (int nb = 0; nb < C::NBW; ++nb) {
+          const int jb = kg * C::NBW + nb;
+          const uint64_t word = (jb & 2) ? vis_hi : vis_lo;
+          const uint32_t vis = (uint32_t)(word >> ((jb & 1) * 32)) >> (4 * g);
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            s[nb][r] = ((vis >> (8 * (r >> 2) + (r & 3))) & 1u) ? s[nb][r] : -INFINITY;
+        }
+      }
+      float m_blk = -INFINITY;
+#pragma unroll
+      for (int nb = 0; nb < C::NBW; ++nb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) m_blk = fmaxf(m_blk, s[nb][r]);
+      m_blk = fmaxf(m_blk, __shfl_xor(m_blk, 32, kWave));
+      const float m_new = fmaxf(m_run, m_blk);
+      const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+      // rescale only when some query of this wave saw a new maximum
+      if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
+        const float alpha = fast_exp2(m_run - m_safe);
+        l_run *= alpha;
 #pragma unroll
         for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-          for (int r = 0; r < 16; ++r)
-            o_acc[mb][r] = o_acc[mb][r] * a1 + slot[(mb * 16 + r) * 64 + lane] * a2;
+          for (int r = 0; r < 16; ++r) o_acc[mb][r] *= alpha;
+        m_run = m_new;
       }
-    }
-  }
-  if (kg != 0 || t >= T) return;
 
-  // ---- write: lane holds d = mb*32 + 8*(r/4) + 4*g + r%4 for its query t
-  if (p.n_split == 1) {
-    const float inv = 1.f / l_run;
-    uint16_t *orow = p.out + ((size_t)unit * p.T_max + t) * kD;
+      // ---- P^T (bf16) straight from the score registers, then O^T += V^T . P^T.
+      //      The A operand V^T comes from row-major V in LDS through the transposing
+      //      read: in each group of 16 lanes, lane i points at row i/4, 4 columns from
+      //      4*(i%4), and receives column i of those 4 rows.
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb)
+      for (int nb = 0; nb < C::NBW; ++nb) {
+        const int jb = kg * C::NBW + nb;
+        uint32_t pw[8];
 #pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        u32x2 w;
-        w.x = pack_bf16x2(o_acc[mb][4 * q4] * inv, o_acc[mb][4 * q4 + 1] * inv);
-        w.y = pack_bf16x2(o_acc[mb][4 * q4 + 2] * inv, o_acc[mb][4 * q4 + 3] * inv);
-        *reinterpret_cast<u32x2 *>(orow + mb * 32 + 8 * q4 + 4 * g) = w;
+        for (int r = 0; r < 16; r += 2) {
+          const float p0 = fast_exp2(s[nb][r] - m_safe), p1 = fast_exp2(s[nb][r + 1] - m_safe);
+          l_run += p0 + p1;
+          pw[r >> 1] = cvt_pk_bf16(p0, p1);
+        }
+#pragma unroll
+        for (int ks2 = 0; ks2 < 2; ++ks2) {
+          const u32x4 pv = {pw[4 * ks2], pw[4 * ks2 + 1], pw[4 * ks2 + 2], pw[4 * ks2 + 3]};
+          const bf16x8 pf = __builtin_bit_cast(bf16x8, pv);
+          // slots 0..3: rows 16*ks2 + 4g + 0..3; slots 4..7: those rows + 8
+          const int row = jb * 32 + 16 * ks2 + 4 * g + ((lane & 15) >> 2);
+          const int col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+#pragma unroll
+          for (int mb = 0; mb < 4; ++mb) {
+            const uint16_t *src = &Vs[row * kVPitch + mb * 32 + col];
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) s16x4 *)(src));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) s16x4 *)(src + 8 * kVPitch));
+            const u32x2 lo2 = __builtin_bit_cast(u32x2, lo), hi2 = __builtin_bit_cast(u32x2, hi);
+            const u32x4 aw = {lo2.x, lo2.y, hi2.x, hi2.y};
+            o_acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, aw), pf,
+                                                                o_acc[mb], 0, 0, 0);
+          }
+        }
       }
-  } else {
-    const size_t slot = (size_t)unit * p.n_split + split;
-    float *po = p.part_o + (slot * 128 + t) * kD;
-#pragma unroll
-    for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        const f32x4 w = {o_acc[mb][4 * q4], o_acc[mb][4 * q4 + 1], o_acc[mb][4 * q4 + 2],
-                         o_acc[mb][4 * q4 + 3]};
-        *reinterpret_cast<f32x4 *>(po + mb * 32 + 8 * q4 + 4 * g) = w;
-      }
-    if (g == 0) {
-      p.part_ml[(slot * 128 + t) * 2] = m_run;
-      p.part_ml[(slot * 128 + t) * 2 + 1] = l_run;
+      __syncthreads();  // tile it is consumed, tile it+1 is visible
     }
+
+    // ---- merge the row groups of one query group through LDS (lane-wise)
+    mfma_settle();
+    l_run += __shfl_xor(l_run, 32, kWave);
+    if (C::KG > 1) {
+      float *mg = reinterpret_cast<float *>(smem);
+      if (kg > 0) {
+        float *slot = mg + (size_t)((kg - 1) * TG + tg) * 66 * 64;
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) slot[(mb * 16 + r) * 64 + lane] = o_acc[mb][r];
+        slot[64 * 64 + lane] = m_run;
+        slot[65 * 64 + lane] = l_run;
+      }
+      __syncthreads();
+      if (kg == 0) {
+#pragma unroll
+        for (int k2 = 1; k2 < C::KG; ++k2) {
+          const float *slot = mg + (size_t)((k2 - 1) * TG + tg) * 66 * 64;
+          const float m2 = slot[64 * 64 + lane], l2 = slot[65 * 64 + lane];
+          const float m_new = fmaxf(m_run, m2);
+          const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+          const float a1 = fast_exp2(m_run - m_safe), a2 = fast_exp2(m2 - m_safe);
+          l_run = l_run * a1 + l2 * a2;
+          m_run = m_new;
+#pragma unroll
+          for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+              o_acc[mb][r] = o_acc[mb][r] * a1 + slot[(mb * 16 + r) * 64 + lane] * a2;
+        }
+      }
+      __syncthreads();  // the buffers are reused by the next segment
+    }
+
+    // ---- write: lane holds d = mb*32 + 8*(r/4) + 4*g + r%4 for its query t
+    if (kg == 0 && t < T) {
+      if (whole) {
+        const float inv = 1.f / l_run;
+        uint16_t *orow = p.out + ((size_t)unit * p.T_max + t) * kD;
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+          for (int q4 = 0; q4 < 4; ++q4) {
+            u32x2 w2;
+            w2.x = cvt_pk_bf16(o_acc[mb][4 * q4] * inv, o_acc[mb][4 * q4 + 1] * inv);
+            w2.y = cvt_pk_bf16(o_acc[mb][4 * q4 + 2] * inv, o_acc[mb][4 * q4 + 3] * inv);
+            *reinterpret_cast<u32x2 *>(orow + mb * 32 + 8 * q4 + 4 * g) = w2;
+          }
+      } else {
+        // a range starts inside at most one unit and ends inside at most one
+        const size_t slot = 2 * (size_t)w + (tile0 > 0 ? 0 : 1);
+        float *po = p.part_o + (slot * 128 + t) * kD;
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+          for (int q4 = 0; q4 < 4; ++q4) {
+            const f32x4 w4 = {o_acc[mb][4 * q4], o_acc[mb][4 * q4 + 1], o_acc[mb][4 * q4 + 2],
+                              o_acc[mb][4 * q4 + 3]};
+            *reinterpret_cast<f32x4 *>(po + mb * 32 + 8 * q4 + 4 * g) = w4;
+          }
+        if (g == 0) {
+          p.part_ml[(slot * 128 + t) * 2] = m_run;
+          p.part_ml[(slot * 128 + t) * 2 + 1] = l_run;
+        }
+      }
+    }
+    x += n_tiles;
   }
 }
 
-// Merge the splits of one (sequence, head): out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
-__global__ __launch_bounds__(kAttnThreads) void tree_attn_combine_kernel(AttnParams p) {
+// Finish the units that a range boundary cut: out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s
+// over the workgroups s that hold a piece.  One workgroup per unit; whole units return at once.
+template <int TILE_J>
+__global__ __launch_bounds__(kAttnThreads) void tree_attn_combine_kernel(AttnParams p, int G) {
   const int unit = blockIdx.x;
-  const int b = unit / p.H;
-  int T = p.n_nodes[b];
-  T = T < 1 ? 1 : (T > p.T_max ? p.T_max : T);
+  const int b = unit / p.H, h = unit - b * p.H;
+  const TileMap<TILE_J> map = {p.B, p.H, p.seq_lens, p.n_nodes, p.L_max, p.T_max};
+  long long n_total = 0, b_start = 0;
+  for (int bb = 0; bb < p.B; ++bb) {
+    if (bb == b) b_start = n_total;
+    n_total += (long long)p.H * map.unit_tiles(bb);
+  }
+  const int ut = map.unit_tiles(b), T = map.nodes(b);
+  const long long S = b_start + (long long)h * ut, E = S + ut;
+  // workgroup that owns tile x: the largest w with range_start(w) <= x
+  auto owner = [&](long long x) {
+    long long w = x * G / n_total;
+    while (w + 1 < G && range_start(w + 1, n_total, G) <= x) ++w;
+    while (w > 0 && range_start(w, n_total, G) > x) --w;
+    return w;
+  };
+  const long long w_first = owner(S), w_last = owner(E - 1);
+  if (w_first == w_last) return;  // the unit was finished by one workgroup
   for (int item = threadIdx.x; item < T * (kD / 4); item += kAttnThreads) {
     const int t = item / (kD / 4), d4 = (item - t * (kD / 4)) * 4;
     float M = -INFINITY;
-    for (int s = 0; s < p.n_split; ++s)
-      M = fmaxf(M, p.part_ml[(((size_t)unit * p.n_split + s) * 128 + t) * 2]);
+    for (long long w = w_first; w <= w_last; ++w) {
+      const size_t slot = 2 * (size_t)w + (range_start(w, n_total, G) > S ? 0 : 1);
+      M = fmaxf(M, p.part_ml[(slot * 128 + t) * 2]);
+    }
     if (M == -INFINITY) M = 0.f;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     float lsum = 0.f;
-    for (int s = 0; s < p.n_split; ++s) {
-      const size_t slot = (size_t)unit * p.n_split + s;
-      const float w = fast_exp2(p.part_ml[(slot * 128 + t) * 2] - M);
-      lsum += w * p.part_ml[(slot * 128 + t) * 2 + 1];
-      if (w != 0.f) {
+    for (long long w = w_first; w <= w_last; ++w) {
+      const size_t slot = 2 * (size_t)w + (range_start(w, n_total, G) > S ? 0 : 1);
+      const float wgt = fast_exp2(p.part_ml[(slot * 128 + t) * 2] - M);
+      lsum += wgt * p.part_ml[(slot * 128 + t) * 2 + 1];
+      if (wgt != 0.f) {
         const f32x4 o = *reinterpret_cast<const f32x4 *>(p.part_o + (slot * 128 + t) * kD + d4);
-        acc += o * w;
+        acc += o * wgt;
       }
     }
     const float inv = 1.f / lsum;
     u32x2 w2;
-    w2.x = pack_bf16x2(acc.x * inv, acc.y * inv);
-    w2.y = pack_bf16x2(acc.z * inv, acc.w * inv);
+    w2.x = cvt_pk_bf16(acc.x * inv, acc.y * inv);
+    w2.y = cvt_pk_bf16(acc.z * inv, acc.w * inv);
     *reinterpret_cast<u32x2 *>(p.out + ((size_t)unit * p.T_max + t) * kD + d4) = w2;
   }
 }
@@ -410,28 +504,37 @@ static int pick_tg(int T_max) { return T_max <= 32 ? 1 : (T_max <= 64 ? 2 : 4); 
 
 static int tile_rows(int tg) { return tg == 1 ? AttnCfg<1>::TILE_J : AttnCfg<4>::TILE_J; }
 
-// KV splits: enough workgroups to cover the chip a few times over, but never
-// fewer than two tiles per split.
-static int pick_splits(int B, int H, int L_max, int T_max) {
-  const long long units = (long long)B * H;
-  const int tile = tile_rows(pick_tg(T_max));
-  const int max_by_len = L_max / (2 * tile) > 1 ? L_max / (2 * tile) : 1;
-  long long want = (1024 + units - 1) / units;
-  if (want < 1) want = 1;
-  if (want > max_by_len) want = max_by_len;
-  if (want > 64) want = 64;
-  return (int)want;
+static int compute_units() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+      cus = prop.multiProcessorCount;
+    if (cus <= 0) cus = 256;
+  }
+  return cus;
 }
 
+// Workgroups of the persistent kernel: two per compute unit (what LDS and registers
+// allow to be resident), fewer when the whole call has fewer than two tiles per workgroup.
+static int pick_grid(int B, int H, int L_max, int T_max) {
+  const int tile = tile_rows(pick_tg(T_max));
+  const long long per_unit = (L_max + tile - 1) / tile + (T_max + tile - 1) / tile;
+  const long long tiles = (long long)B * H * per_unit;
+  long long grid = 2ll * compute_units();
+  if (grid > (tiles + 1) / 2) grid = (tiles + 1) / 2;
+  return (int)(grid < 1 ? 1 : grid);
+}
+
+// Partial slots: two per workgroup of the grid this call will use.
 size_t tree_attention_workspace_bytes(int B, int H, int L_max, int T_max) {
-  const int ns = pick_splits(B, H, L_max, T_max);
-  if (ns == 1) return 256;
-  const size_t slots = (size_t)B * H * ns;
+  const size_t slots = 2 * (size_t)pick_grid(B, H, L_max, T_max);
   return align_up(slots * 128 * kD * 4, 256) + align_up(slots * 128 * 2 * 4, 256);
 }
 
 template <int TG>
-static bool launch_bf16(const AttnParams &p, int units, hipStream_t st) {
+static bool launch_bf16(const AttnParams &p, int grid, int units, hipStream_t st) {
   static bool attr_set = false;
   if (!attr_set) {
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_attn_bf16_kernel<TG>),
@@ -440,8 +543,11 @@ static bool launch_bf16(const AttnParams &p, int units, hipStream_t st) {
       return false;
     attr_set = true;
   }
-  hipLaunchKernelGGL(tree_attn_bf16_kernel<TG>, dim3((unsigned)(units * p.n_split)),
-                     dim3(kAttnThreads), AttnCfg<TG>::lds_bytes, st, p);
+  hipLaunchKernelGGL(tree_attn_bf16_kernel<TG>, dim3((unsigned)grid), dim3(kAttnThreads),
+                     AttnCfg<TG>::lds_bytes, st, p);
+  if (!launch_ok()) return false;
+  hipLaunchKernelGGL(tree_attn_combine_kernel<AttnCfg<TG>::TILE_J>, dim3((unsigned)units),
+                     dim3(kAttnThreads), 0, st, p, grid);
   return launch_ok();
 }
 
@@ -502,24 +608,20 @@ extern "C" propd_status propd_tree_attention(const propd_tree *tree, propd_dtype
   p.H = H;
   p.T_max = tree->T_max;
   p.L_max = L_max;
-  p.n_split = pick_splits(tree->B, H, L_max, tree->T_max);
+  p.B = tree->B;
   p.scale_log2e = scale * 1.4426950408889634f;
-  const size_t slots = (size_t)units * p.n_split;
+  const int grid = pick_grid(tree->B, H, L_max, tree->T_max);
+  const size_t slots = 2 * (size_t)grid;
   p.part_o = reinterpret_cast<float *>(workspace);
   p.part_ml = reinterpret_cast<float *>(reinterpret_cast<char *>(workspace) +
                                         align_up(slots * 128 * kD * 4, 256));
   bool ok;
   switch (pick_tg(tree->T_max)) {
-    case 1: ok = launch_bf16<1>(p, (int)units, st); break;
-    case 2: ok = launch_bf16<2>(p, (int)units, st); break;
-    default: ok = launch_bf16<4>(p, (int)units, st); break;
+    case 1: ok = launch_bf16<1>(p, grid, (int)units, st); break;
+    case 2: ok = launch_bf16<2>(p, grid, (int)units, st); break;
+    default: ok = launch_bf16<4>(p, grid, (int)units, st); break;
   }
   if (!ok) return PROPD_ERR_DEVICE;
-  if (p.n_split > 1) {
-    hipLaunchKernelGGL(tree_attn_combine_kernel, dim3((unsigned)units), dim3(kAttnThreads), 0, st,
-                       p);
-    if (!launch_ok()) return PROPD_ERR_DEVICE;
-  }
   return PROPD_OK;
 }
 
