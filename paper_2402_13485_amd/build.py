@@ -18,7 +18,8 @@ FLAGS = [
 
 def build(verbose: bool = False) -> str:
     srcs = [os.path.join(CSRC, s) for s in SOURCES]
-    cmd = ["hipcc", *FLAGS, "-DPROPD_BUILD", "-o", LIB_PATH, *srcs]
+    extra = os.environ.get("PROPD_EXTRA_HIPCC_FLAGS", "").split()  # tuning experiments only
+    cmd = ["hipcc", *FLAGS, *extra, "-DPROPD_BUILD", "-o", LIB_PATH, *srcs]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)

@@ -142,100 +142,138 @@ __global__ __launch_bounds__(kScanThreads) void cu_nodes_kernel(int B,
 // ------------------------------------------------------------------------------------
 // C[m][v] = sum_x A[m][x] * W[v][x].  Both operands are contiguous along x, which is
 // the layout the 32x32x16 MFMA wants (8 consecutive x per lane), so tiles go
-// global -> LDS -> registers without any transpose.  Workgroup tile 128 x 128,
-// K step 64, four waves in a 2 x 2 arrangement, each owning a 64 x 64 block
-// (2 x 2 MFMA tiles, 64 accumulator registers).  The next K step is fetched into
-// registers while the current one is multiplied.
-constexpr int kBM = 128, kBN = 128, kBK = 64, kPitch = kBK + 8;  // pitch 144 B: conflict-free b128
+// global -> registers -> LDS -> MFMA operands without any transpose.
+//   - workgroup tile BM x BN, K step 64, four waves in a 2 x 2 arrangement, each
+//     owning (BM/2) x (BN/2) as FM x FN MFMA tiles of 32 x 32;
+//   - LDS is double buffered: one barrier per K step, the step after next is in
+//     flight (in registers) while the current one is multiplied;
+//   - the grid is one-dimensional and XCD-aware.  Workgroups are handed to the 8
+//     XCDs round-robin, each XCD has its own L2: workgroup id -> (xcd, slot), and an
+//     XCD walks its own vocabulary tiles with all row tiles of one vocabulary tile
+//     adjacent in time, so a weight tile is fetched from HBM once and hits in that
+//     XCD's L2 for the other row tiles.
+constexpr int kBK = 64, kPitch = kBK + 8;  // pitch 144 B: conflict-free b128 reads
 constexpr int kGemmThreads = 256;
+constexpr int kXcds = 8;
+#ifndef PROPD_GEMM_BM
+#define PROPD_GEMM_BM 128
+#define PROPD_GEMM_BN 128
+#endif
 
+template <int BM, int BN>
+struct GemmCfg {
+  static constexpr int FM = BM / 64, FN = BN / 64;    // 32x32 tiles per wave
+  static constexpr int LA = BM / 32, LB = BN / 32;    // 16-byte chunks per thread per K step
+  static constexpr int stage_elems = (BM + BN) * kPitch;
+  static constexpr size_t lds_bytes = 2 * (size_t)stage_elems * 2;
+};
+
+template <int BM, int BN>
 __global__ __launch_bounds__(kGemmThreads) void early_head_bf16_kernel(
     int hidden, int vocab, int B, const uint16_t *__restrict__ hidden_states,
     const uint16_t *__restrict__ head_weight, const int32_t *__restrict__ row_src,
     const int32_t *__restrict__ row_base, float *__restrict__ scores, size_t score_pitch) {
+  using C = GemmCfg<BM, BN>;
   const int m_total = row_base[B];
-  const int m0 = blockIdx.x * kBM, v0 = blockIdx.y * kBN;
-  if (m0 >= m_total) return;
+  const int m_tiles = (m_total + BM - 1) / BM;
+  const int n_tiles = (vocab + BN - 1) / BN;
+  const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+  const int n_tile = (slot / (m_tiles > 0 ? m_tiles : 1)) * kXcds + xcd;
+  if (m_tiles == 0 || n_tile >= n_tiles) return;
+  const int m0 = (slot % m_tiles) * BM, v0 = n_tile * BN;
 
-  __shared__ __attribute__((aligned(16))) uint16_t As[kBM * kPitch];
-  __shared__ __attribute__((aligned(16))) uint16_t Bs[kBN * kPitch];
+  extern __shared__ __attribute__((aligned(16))) unsigned char gemm_smem[];
+  uint16_t *lds = reinterpret_cast<uint16_t *>(gemm_smem);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int l32 = lane & 31, g = lane >> 5;
 
-  // each thread moves four 16-byte chunks of A and of B per K step
+  // thread -> (row, 8 columns) of a 32-row slab; LA slabs of A and LB slabs of B per K step
   const int ld_row = tid >> 3, ld_col = (tid & 7) * 8;
-  const uint16_t *a_ptr[4];
-  const uint16_t *b_ptr[4];
+  const uint16_t *a_ptr[C::LA];
+  const uint16_t *b_ptr[C::LB];
 #pragma unroll
-  for (int it = 0; it < 4; ++it) {
-    const int row = it * 32 + ld_row;
-    const int m = m0 + row, v = v0 + row;
+  for (int it = 0; it < C::LA; ++it) {
+    const int m = m0 + it * 32 + ld_row;
     a_ptr[it] = m < m_total ? hidden_states + (size_t)row_src[m] * hidden + ld_col : nullptr;
+  }
+#pragma unroll
+  for (int it = 0; it < C::LB; ++it) {
+    const int v = v0 + it * 32 + ld_row;
     b_ptr[it] = v < vocab ? head_weight + (size_t)v * hidden + ld_col : nullptr;
   }
   const u32x4 zero4 = {0u, 0u, 0u, 0u};
-  u32x4 a_reg[4], b_reg[4];
+  u32x4 a_reg[C::LA], b_reg[C::LB];
   auto fetch = [&](int k0) {
 #pragma unroll
-    for (int it = 0; it < 4; ++it) {
+    for (int it = 0; it < C::LA; ++it)
       a_reg[it] = a_ptr[it] ? *reinterpret_cast<const u32x4 *>(a_ptr[it] + k0) : zero4;
-      b_reg[it] = b_ptr[it] ? *reinterpret_cast<const u32x4 *>(b_ptr[it] + k0) : zero4;
-    }
-  };
-  auto stash = [&]() {
 #pragma unroll
-    for (int it = 0; it < 4; ++it) {
-      const int row = it * 32 + ld_row;
-      *reinterpret_cast<u32x4 *>(&As[row * kPitch + ld_col]) = a_reg[it];
-      *reinterpret_cast<u32x4 *>(&Bs[row * kPitch + ld_col]) = b_reg[it];
-    }
+    for (int it = 0; it < C::LB; ++it)
+      b_reg[it] = b_ptr[it] ? *reinterpret_cast<const u32x4 *>(b_ptr[it] + k0) : zero4;
+  };
+  auto stash = [&](int buf) {
+    uint16_t *As = lds + buf * C::stage_elems;
+    uint16_t *Bs = As + BM * kPitch;
+#pragma unroll
+    for (int it = 0; it < C::LA; ++it)
+      *reinterpret_cast<u32x4 *>(&As[(it * 32 + ld_row) * kPitch + ld_col]) = a_reg[it];
+#pragma unroll
+    for (int it = 0; it < C::LB; ++it)
+      *reinterpret_cast<u32x4 *>(&Bs[(it * 32 + ld_row) * kPitch + ld_col]) = b_reg[it];
   };
 
-  f32x16 acc[2][2];
+  f32x16 acc[C::FM][C::FN];
 #pragma unroll
-  for (int x = 0; x < 2; ++x)
+  for (int x = 0; x < C::FM; ++x)
 #pragma unroll
-    for (int y = 0; y < 2; ++y)
+    for (int y = 0; y < C::FN; ++y)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
 
+  const int n_steps = hidden / kBK;
   fetch(0);
-  for (int k0 = 0; k0 < hidden; k0 += kBK) {
-    __syncthreads();  // previous step's reads are done
-    stash();
-    __syncthreads();
-    if (k0 + kBK < hidden) fetch(k0 + kBK);
+  stash(0);
+  if (n_steps > 1) fetch(kBK);
+  __syncthreads();
+  for (int step = 0; step < n_steps; ++step) {
+    const int cur = step & 1;
+    if (step + 1 < n_steps) stash(cur ^ 1);
+    if (step + 2 < n_steps) fetch((step + 2) * kBK);
+    const uint16_t *As = lds + cur * C::stage_elems;
+    const uint16_t *Bs = As + BM * kPitch;
 #pragma unroll
     for (int ks = 0; ks < kBK / 16; ++ks) {
-      bf16x8 af[2], bf[2];
+      bf16x8 af[C::FM], bf[C::FN];
 #pragma unroll
-      for (int x = 0; x < 2; ++x) {
+      for (int x = 0; x < C::FM; ++x)
         af[x] = *reinterpret_cast<const bf16x8 *>(
-            &As[(wm * 64 + x * 32 + l32) * kPitch + ks * 16 + g * 8]);
-        bf[x] = *reinterpret_cast<const bf16x8 *>(
-            &Bs[(wn * 64 + x * 32 + l32) * kPitch + ks * 16 + g * 8]);
-      }
+            &As[(wm * (BM / 2) + x * 32 + l32) * kPitch + ks * 16 + g * 8]);
 #pragma unroll
-      for (int x = 0; x < 2; ++x)
+      for (int y = 0; y < C::FN; ++y)
+        bf[y] = *reinterpret_cast<const bf16x8 *>(
+            &Bs[(wn * (BN / 2) + y * 32 + l32) * kPitch + ks * 16 + g * 8]);
 #pragma unroll
-        for (int y = 0; y < 2; ++y)
+      for (int x = 0; x < C::FM; ++x)
+#pragma unroll
+        for (int y = 0; y < C::FN; ++y)
           acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[x], bf[y], acc[x][y], 0, 0, 0);
     }
+    __syncthreads();
   }
 
   mfma_settle();
   // accumulator layout of the 32x32 MFMA: lane -> column l32, register r -> row
   // 8*(r/4) + 4*g + r%4
 #pragma unroll
-  for (int x = 0; x < 2; ++x)
+  for (int x = 0; x < C::FM; ++x)
 #pragma unroll
-    for (int y = 0; y < 2; ++y) {
-      const int col = v0 + wn * 64 + y * 32 + l32;
+    for (int y = 0; y < C::FN; ++y) {
+      const int col = v0 + wn * (BN / 2) + y * 32 + l32;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int row = m0 + wm * 64 + x * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+        const int row = m0 + wm * (BM / 2) + x * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
         if (row < m_total && col < vocab) scores[(size_t)row * score_pitch + col] = acc[x][y][r];
       }
     }
@@ -536,8 +574,23 @@ extern "C" propd_status propd_early_prune(
     hipLaunchKernelGGL(row_table_kernel, dim3(1), dim3(kScanThreads), 0, st, B, T_max, ws.n_par,
                        ws.local_list, ws.row_base, ws.row_src);
     if (dt == PROPD_BF16) {
-      dim3 grid((unsigned)((ws.row_cap + kBM - 1) / kBM), (unsigned)((vocab + kBN - 1) / kBN));
-      hipLaunchKernelGGL(early_head_bf16_kernel, grid, dim3(kGemmThreads), 0, st, hidden, vocab, B,
+      constexpr int BM = PROPD_GEMM_BM, BN = PROPD_GEMM_BN;
+      static bool attr_set = false;
+      if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&early_head_bf16_kernel<BM, BN>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)GemmCfg<BM, BN>::lds_bytes) != hipSuccess)
+          return PROPD_ERR_DEVICE;
+        attr_set = true;
+      }
+      const long long m_tiles_cap = (ws.row_cap + BM - 1) / BM;
+      const long long n_groups = ((vocab + BN - 1) / BN + kXcds - 1) / kXcds;
+      const long long grid = kXcds * n_groups * m_tiles_cap;
+      if (grid > (1ll << 31) - 1) return PROPD_ERR_UNSUPPORTED;
+      const size_t lds_bytes = GemmCfg<BM, BN>::lds_bytes;
+      auto kern = early_head_bf16_kernel<BM, BN>;
+      hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kGemmThreads), lds_bytes, st, hidden,
+                         vocab, B,
                          reinterpret_cast<const uint16_t *>(hidden_states),
                          reinterpret_cast<const uint16_t *>(head_weight), ws.row_src, ws.row_base,
                          ws.scores, ws.score_pitch);
