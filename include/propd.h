@@ -116,6 +116,7 @@ PROPD_API propd_status propd_tree_mask(int32_t B, int32_t T_max, const int32_t *
  *   q, k_tree, v_tree, out   [B,H,T_max,d]
  *   k_cache, v_cache         [B,H,L_max,d]; rows >= L_b are never used
  *   seq_lens  [B], 0 <= L_b <= L_max
+ *   scale     softmax scale, must be > 0 (1/sqrt(d) in every workload here)
  *   tree      n_nodes and anc are read (token, parent, depth may be NULL)
  *   out       rows i >= T_b are left untouched
  *   workspace propd_workspace_bytes(PROPD_WS_TREE_ATTENTION, ...) bytes

@@ -4,20 +4,23 @@
 // bf16 path (d = 128).  The work is a stream of K/V rows from HBM that all T
 // tree queries of a (sequence, head) pair share, so the kernel is organised
 // around reading every K and V row exactly once:
-//   - one workgroup (4 waves) per (sequence, head, KV split); K/V tiles go
-//     global -> registers (prefetched one tile ahead) -> LDS, 16 bytes per lane,
-//     fully coalesced;
+//   - a persistent grid (two workgroups of 4 waves per compute unit); the list of
+//     all K/V tiles of the call is cut into equal contiguous ranges, one per
+//     workgroup, so ragged sequence lengths balance by construction;
+//   - K/V tiles go global -> registers -> LDS, 16 bytes per lane, fully coalesced,
+//     double buffered: one barrier per tile, the tile after next in flight;
 //   - scores are computed transposed, S^T = K . Q^T, with the 32x32x16 bf16 MFMA,
 //     so that a lane owns one query column: the running max / sum of the online
 //     softmax are per-lane scalars, and the fp32 score registers, once
 //     exponentiated and rounded to bf16, ARE the B operand of the second MFMA
-//     O^T += V^T . P^T, with no shuffle or LDS round trip;
+//     O^T += V^T . P^T, with no shuffle or LDS round trip; V^T is read from
+//     row-major V in LDS with the transposing LDS read;
 //   - the cached prefix needs no mask; the tree part is one extra tile whose
 //     scores are kept only where the node's 128-bit ancestor set has the bit;
 //   - waves split the query columns (32 per wave) and, when the tree is small,
 //     also the rows of a tile; row groups are merged through LDS at the end;
-//   - a split writes an fp32 partial (O, max, sum); a second kernel merges
-//     splits.  With one split the result is written directly.
+//   - a unit cut by a range boundary leaves fp32 partials (O, max, sum), at most
+//     two per workgroup; a second kernel merges them.
 // fp32 path: a plain one-wave-per-query kernel, fp32 throughout.
 #include "common.h"
 
@@ -25,6 +28,7 @@ namespace propd {
 
 constexpr int kD = 128;
 constexpr int kAttnThreads = 256;
+constexpr int kMaxGrid = 1024;  // workgroups of the persistent kernel, at most
 constexpr int kKPitch = kD + 8;   // bf16 elements per K row in LDS: 272 B, conflict-free b128 reads
 constexpr int kVPitch = kD + 32;  // bf16 elements per V row in LDS: 320 B, conflict-free transpose reads
 
@@ -228,12 +232,9 @@ __global__ __launch_bounds__(kAttnThreads, TG == 1 ? 1 : 2) void tree_attn_bf16_
       }
       mfma_settle();
 
-      // ---- scale (log2 domain), mask, running max.  Register r of a 32x32 accumulator
-      //      holds row 8*(r/4) + 4*g + r%4 of the block, i.e. K/V row j of the tile.
-#pragma unroll
-      for (int nb = 0; nb < C::NBW; ++nb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[nb][r] *= p.scale_log2e;
+      // ---- mask and running max on the raw scores (the softmax scale is positive, so it
+      //      commutes with max and is applied inside the exponent).  Register r of a 32x32
+      //      accumulator holds row 8*(r/4) + 4*g + r%4 of the block, i.e. K/V row j of the tile.
       if (partial) {
         // tile-local visibility of this lane's query: cached rows below L for every
         // query, tree rows only where the node's ancestor set has the bit
@@ -263,7 +264,7 @@ __global__ __launch_bounds__(kAttnThreads, TG == 1 ? 1 : 2) void tree_attn_bf16_
       const float m_safe = m_new == -INFINITY ? 0.f : m_new;
       // rescale only when some query of this wave saw a new maximum
       if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
-        const float alpha = fast_exp2(m_run - m_safe);
+        const float alpha = fast_exp2((m_run - m_safe) * p.scale_log2e);
         l_run *= alpha;
 #pragma unroll
         for (int mb = 0; mb < 4; ++mb)
@@ -271,20 +272,25 @@ __global__ __launch_bounds__(kAttnThreads, TG == 1 ? 1 : 2) void tree_attn_bf16_
           for (int r = 0; r < 16; ++r) o_acc[mb][r] *= alpha;
         m_run = m_new;
       }
+      const float neg_m = -m_safe * p.scale_log2e;
 
       // ---- P^T (bf16) straight from the score registers, then O^T += V^T . P^T.
       //      The A operand V^T comes from row-major V in LDS through the transposing
       //      read: in each group of 16 lanes, lane i points at row i/4, 4 columns from
-      //      4*(i%4), and receives column i of those 4 rows.
+      //      4*(i%4), and receives column i of those 4 rows.  The row sums are taken over
+      //      the rounded bf16 weights, the same values the MFMA multiplies.
+      const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3f803f80u);
 #pragma unroll
       for (int nb = 0; nb < C::NBW; ++nb) {
         const int jb = kg * C::NBW + nb;
         uint32_t pw[8];
 #pragma unroll
         for (int r = 0; r < 16; r += 2) {
-          const float p0 = fast_exp2(s[nb][r] - m_safe), p1 = fast_exp2(s[nb][r + 1] - m_safe);
-          l_run += p0 + p1;
+          const float p0 = fast_exp2(fmaf(s[nb][r], p.scale_log2e, neg_m));
+          const float p1 = fast_exp2(fmaf(s[nb][r + 1], p.scale_log2e, neg_m));
           pw[r >> 1] = cvt_pk_bf16(p0, p1);
+          l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pw[r >> 1]), ones,
+                                                  l_run, false);
         }
 #pragma unroll
         for (int ks2 = 0; ks2 < 2; ++ks2) {
@@ -313,6 +319,7 @@ __global__ __launch_bounds__(kAttnThreads, TG == 1 ? 1 : 2) void tree_attn_bf16_
     // ---- merge the row groups of one query group through LDS (lane-wise)
     mfma_settle();
     l_run += __shfl_xor(l_run, 32, kWave);
+    m_run *= p.scale_log2e;  // from here on the maximum is in the exponent's (log2) domain
     if (C::KG > 1) {
       float *mg = reinterpret_cast<float *>(smem);
       if (kg > 0) {
@@ -404,18 +411,24 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_combine_kernel(AttnPar
   };
   const long long w_first = owner(S), w_last = owner(E - 1);
   if (w_first == w_last) return;  // the unit was finished by one workgroup
+  // partial slots of the pieces, worked out once per workgroup
+  __shared__ int s_slot[kMaxGrid];
+  const int pieces = (int)(w_last - w_first + 1);
+  for (int i = threadIdx.x; i < pieces; i += kAttnThreads) {
+    const long long w = w_first + i;
+    s_slot[i] = (int)(2 * w + (range_start(w, n_total, G) > S ? 0 : 1));
+  }
+  __syncthreads();
   for (int item = threadIdx.x; item < T * (kD / 4); item += kAttnThreads) {
     const int t = item / (kD / 4), d4 = (item - t * (kD / 4)) * 4;
     float M = -INFINITY;
-    for (long long w = w_first; w <= w_last; ++w) {
-      const size_t slot = 2 * (size_t)w + (range_start(w, n_total, G) > S ? 0 : 1);
-      M = fmaxf(M, p.part_ml[(slot * 128 + t) * 2]);
-    }
+    for (int i = 0; i < pieces; ++i)
+      M = fmaxf(M, p.part_ml[((size_t)s_slot[i] * 128 + t) * 2]);
     if (M == -INFINITY) M = 0.f;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     float lsum = 0.f;
-    for (long long w = w_first; w <= w_last; ++w) {
-      const size_t slot = 2 * (size_t)w + (range_start(w, n_total, G) > S ? 0 : 1);
+    for (int i = 0; i < pieces; ++i) {
+      const size_t slot = (size_t)s_slot[i];
       const float wgt = fast_exp2(p.part_ml[(slot * 128 + t) * 2] - M);
       lsum += wgt * p.part_ml[(slot * 128 + t) * 2 + 1];
       if (wgt != 0.f) {
@@ -523,6 +536,7 @@ static int pick_grid(int B, int H, int L_max, int T_max) {
   const long long per_unit = (L_max + tile - 1) / tile + (T_max + tile - 1) / tile;
   const long long tiles = (long long)B * H * per_unit;
   long long grid = 2ll * compute_units();
+  if (grid > kMaxGrid) grid = kMaxGrid;
   if (grid > (tiles + 1) / 2) grid = (tiles + 1) / 2;
   return (int)(grid < 1 ? 1 : grid);
 }
@@ -566,6 +580,7 @@ extern "C" propd_status propd_tree_attention(const propd_tree *tree, propd_dtype
       (L_max > 0 && (!k_cache || !v_cache)))
     return PROPD_ERR_INVALID_ARG;
   if (dt != PROPD_BF16 && dt != PROPD_F32) return PROPD_ERR_INVALID_ARG;
+  if (!(scale > 0.f)) return PROPD_ERR_INVALID_ARG;  // the kernels take max before scaling
   const long long units = (long long)tree->B * H;
   if (units * tree->T_max > (1ll << 30)) return PROPD_ERR_UNSUPPORTED;
   hipStream_t st = as_stream(hip_stream);
