@@ -299,14 +299,18 @@ __global__ __launch_bounds__(256) void early_head_f32_kernel(
 // top-k membership by counting
 // ------------------------------------------------------------------------------------
 constexpr int kRankThreads = 256;
-constexpr int kRankChunk = 8;
+constexpr int kRankChunk = 8;     // children compared per pass over the scores
+constexpr int kRankSplit = 8;     // workgroups sharing one parent row (column slices)
 
+// One parent row is shared by kRankSplit workgroups, each counting over its own slice of
+// the vocabulary and adding its counts to the children's ranks with integer atomics (the
+// sum does not depend on the order).  ranks of children were zeroed by parent_rows_kernel.
 __global__ __launch_bounds__(kRankThreads) void rank_count_kernel(
     int B, int T_max, int vocab, const int32_t *__restrict__ n_nodes,
     const int32_t *__restrict__ parent, const int32_t *__restrict__ token,
     const int32_t *__restrict__ row_src, const int32_t *__restrict__ row_base,
     const float *__restrict__ scores, size_t score_pitch, int32_t *__restrict__ rank) {
-  const int m = blockIdx.x;
+  const int m = blockIdx.x / kRankSplit, part = blockIdx.x - m * kRankSplit;
   if (m >= row_base[B]) return;
   const int node = row_src[m];
   const int b = node / T_max, p = node - b * T_max;
@@ -323,7 +327,10 @@ __global__ __launch_bounds__(kRankThreads) void rank_count_kernel(
   __syncthreads();
   const int nchild = s_nchild;
   const float *z = scores + (size_t)m * score_pitch;
+  // this workgroup's slice, in units of 4 scores; the last slice also takes the tail
   const int nvec = vocab >> 2;
+  const int per = (nvec + kRankSplit - 1) / kRankSplit;
+  const int c_lo = part * per, c_hi = (c_lo + per < nvec) ? c_lo + per : nvec;
 
   for (int c0 = 0; c0 < nchild; c0 += kRankChunk) {
     float thr[kRankChunk];
@@ -344,7 +351,7 @@ __global__ __launch_bounds__(kRankThreads) void rank_count_kernel(
     }
     if (tid < kRankChunk) s_count[tid] = 0;
     __syncthreads();
-    for (int c = tid; c < nvec; c += kRankThreads) {
+    for (int c = c_lo + tid; c < c_hi; c += kRankThreads) {
       const f32x4 u = *reinterpret_cast<const f32x4 *>(z + 4 * c);
       const int v = 4 * c;
 #pragma unroll
@@ -355,24 +362,35 @@ __global__ __launch_bounds__(kRankThreads) void rank_count_kernel(
         cnt[e] += (u.w > thr[e]) || (u.w == thr[e] && v + 3 < tok[e]);
       }
     }
-    for (int v = 4 * nvec + tid; v < vocab; v += kRankThreads) {
-      const float x = z[v];
+    if (part == kRankSplit - 1)
+      for (int v = 4 * nvec + tid; v < vocab; v += kRankThreads) {
+        const float x = z[v];
 #pragma unroll
-      for (int e = 0; e < kRankChunk; ++e) cnt[e] += (x > thr[e]) || (x == thr[e] && v < tok[e]);
-    }
+        for (int e = 0; e < kRankChunk; ++e)
+          cnt[e] += (x > thr[e]) || (x == thr[e] && v < tok[e]);
+      }
 #pragma unroll
     for (int e = 0; e < kRankChunk; ++e) {
-      const int s = wave_reduce_sum(cnt[e]);
-      if ((tid & 63) == 0 && s) atomicAdd(&s_count[e], s);
+      const int sum = wave_reduce_sum(cnt[e]);
+      if ((tid & 63) == 0 && sum) atomicAdd(&s_count[e], sum);
     }
     __syncthreads();
     if (tid < kRankChunk && c0 + tid < nchild) {
-      // a token id outside the vocabulary can be in no top-k list
-      int mine = vocab;
+      int mine = 0;
+      bool valid_tok = false;
 #pragma unroll
       for (int e = 0; e < kRankChunk; ++e)
-        if (e == tid && tok[e] >= 0) mine = s_count[e];
-      rank[(size_t)b * T_max + s_child[c0 + tid]] = mine;
+        if (e == tid) {
+          mine = s_count[e];
+          valid_tok = tok[e] >= 0;
+        }
+      int32_t *dst = &rank[(size_t)b * T_max + s_child[c0 + tid]];
+      // a token id outside the vocabulary can be in no top-k list
+      if (!valid_tok) {
+        if (part == 0) atomicAdd(dst, vocab);
+      } else if (mine) {
+        atomicAdd(dst, mine);
+      }
     }
     __syncthreads();
   }
@@ -474,34 +492,35 @@ struct PayloadArgs {
 
 constexpr int kGatherThreads = 256;
 
-// One wave per destination row (b, o, j); blockIdx.y selects the payload.
+// One workgroup per (b, o) pair of a payload (blockIdx.y selects the payload); its four
+// waves walk the survivors j = wave, wave + 4, ... and copy one row each, 16 bytes per lane.
 __global__ __launch_bounds__(kGatherThreads) void gather_rows_kernel(
     PayloadArgs args, int B, int T_max, const int32_t *__restrict__ orig_index,
     const int32_t *__restrict__ n_kept) {
   const int pl = blockIdx.y;
   const long long outer = args.outer[pl];
-  const long long rows = (long long)B * outer * T_max;
-  const long long row = (long long)blockIdx.x * (kGatherThreads / kWave) + (threadIdx.x >> 6);
-  if (row >= rows) return;
-  const int j = (int)(row % T_max);
-  const long long bo = row / T_max;
+  const long long bo = blockIdx.x;
+  if (bo >= (long long)B * outer) return;
   const long long o = bo % outer;
   const int b = (int)(bo / outer);
-  if (j >= n_kept[b]) return;
-  const int i = orig_index[(size_t)b * T_max + j];
-  if (i < 0 || i >= T_max) return;
-  const char *s = args.src[pl] + b * args.stride_b[pl] + o * args.stride_outer[pl] +
-                  (long long)i * args.stride_t[pl];
-  char *d = args.dst[pl] + b * args.stride_b[pl] + o * args.stride_outer[pl] +
-            (long long)j * args.stride_t[pl];
+  int kept = n_kept[b];
+  kept = kept > T_max ? T_max : kept;
+  const char *sbase = args.src[pl] + b * args.stride_b[pl] + o * args.stride_outer[pl];
+  char *dbase = args.dst[pl] + b * args.stride_b[pl] + o * args.stride_outer[pl];
   const unsigned long long nbytes = args.row_bytes[pl];
   const int lane = threadIdx.x & 63;
-  if (args.vec16[pl]) {
-    const unsigned long long n16 = nbytes >> 4;
-    for (unsigned long long c = lane; c < n16; c += kWave)
-      reinterpret_cast<u32x4 *>(d)[c] = reinterpret_cast<const u32x4 *>(s)[c];
-  } else {
-    for (unsigned long long c = lane; c < nbytes; c += kWave) d[c] = s[c];
+  for (int j = threadIdx.x >> 6; j < kept; j += kGatherThreads / kWave) {
+    const int i = orig_index[(size_t)b * T_max + j];
+    if (i < 0 || i >= T_max) continue;
+    const char *s = sbase + (long long)i * args.stride_t[pl];
+    char *d = dbase + (long long)j * args.stride_t[pl];
+    if (args.vec16[pl]) {
+      const unsigned long long n16 = nbytes >> 4;
+      for (unsigned long long c = lane; c < n16; c += kWave)
+        reinterpret_cast<u32x4 *>(d)[c] = reinterpret_cast<const u32x4 *>(s)[c];
+    } else {
+      for (unsigned long long c = lane; c < nbytes; c += kWave) d[c] = s[c];
+    }
   }
 }
 
@@ -535,7 +554,7 @@ extern "C" propd_status propd_early_prune(
     return PROPD_ERR_INVALID_ARG;
   if (dt == PROPD_BF16 && hidden % kBK != 0) return PROPD_ERR_UNSUPPORTED;
   const int B = tree->B, T_max = tree->T_max;
-  if ((long long)B * T_max > (1ll << 30)) return PROPD_ERR_UNSUPPORTED;
+  if ((long long)B * T_max > (1ll << 27)) return PROPD_ERR_UNSUPPORTED;
   long long max_rows = 0;
   PayloadArgs pa = {};
   for (int p = 0; p < n_payloads; ++p) {
@@ -554,8 +573,8 @@ extern "C" propd_status propd_early_prune(
                           (uintptr_t)pl.row_bytes | (uintptr_t)pl.stride_b |
                           (uintptr_t)pl.stride_outer | (uintptr_t)pl.stride_t;
     pa.vec16[p] = (any & 15) == 0;
-    const long long rows = (long long)B * pl.outer * T_max;
-    if (rows > (1ll << 31)) return PROPD_ERR_UNSUPPORTED;
+    const long long rows = (long long)B * pl.outer;  // one workgroup per (b, o)
+    if (rows > (1ll << 31) - 1) return PROPD_ERR_UNSUPPORTED;
     max_rows = rows > max_rows ? rows : max_rows;
   }
   const size_t need = early_prune_workspace_bytes(B, T_max, vocab);
@@ -601,7 +620,7 @@ extern "C" propd_status propd_early_prune(
                          reinterpret_cast<const float *>(head_weight), ws.row_src, ws.row_base,
                          ws.scores, ws.score_pitch);
     }
-    hipLaunchKernelGGL(rank_count_kernel, dim3((unsigned)ws.row_cap), dim3(kRankThreads), 0, st, B,
+    hipLaunchKernelGGL(rank_count_kernel, dim3((unsigned)(ws.row_cap * kRankSplit)), dim3(kRankThreads), 0, st, B,
                        T_max, vocab, tree->n_nodes, tree->parent, tree->token, ws.row_src,
                        ws.row_base, ws.scores, ws.score_pitch, ws.rank);
   }
@@ -612,8 +631,7 @@ extern "C" propd_status propd_early_prune(
                      tree_out->token, tree_out->depth, tree_out->anc, rank_out);
   hipLaunchKernelGGL(cu_nodes_kernel, dim3(1), dim3(kScanThreads), 0, st, B, n_kept, cu_nodes);
   if (n_payloads > 0) {
-    const unsigned per_block = kGatherThreads / kWave;
-    dim3 grid((unsigned)((max_rows + per_block - 1) / per_block), (unsigned)n_payloads);
+    dim3 grid((unsigned)max_rows, (unsigned)n_payloads);
     hipLaunchKernelGGL(gather_rows_kernel, grid, dim3(kGatherThreads), 0, st, pa, B, T_max,
                        orig_index, n_kept);
   }

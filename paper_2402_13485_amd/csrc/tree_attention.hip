@@ -26,6 +26,9 @@
 
 namespace propd {
 
+#ifndef PROPD_EXP
+#define PROPD_EXP 0  // timing experiments: 1 no S MFMAs, 2 no exp, 4 no PV, 8 no settle
+#endif
 constexpr int kD = 128;
 constexpr int kAttnThreads = 256;
 constexpr int kMaxGrid = 1024;  // workgroups of the persistent kernel, at most
@@ -222,15 +225,16 @@ __global__ __launch_bounds__(kAttnThreads, TG == 1 ? 1 : 2) void tree_attn_bf16_
       for (int nb = 0; nb < C::NBW; ++nb) {
         const int jb = kg * C::NBW + nb;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s[nb][r] = 0.f;
+        for (int r = 0; r < 16; ++r)
+          s[nb][r] = (PROPD_EXP & 1) ? (float)__builtin_bit_cast(u32x4, qf[r & 7]).x * 1e-12f : 0.f;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
+        for (int ks = 0; ks < ((PROPD_EXP & 1) ? 0 : 8); ++ks) {
           const bf16x8 a =
               *reinterpret_cast<const bf16x8 *>(&Ks[(jb * 32 + l32) * kKPitch + ks * 16 + g * 8]);
           s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[nb], 0, 0, 0);
         }
       }
-      mfma_settle();
+      if (!(PROPD_EXP & 8)) mfma_settle();
 
       // ---- mask and running max on the raw scores (the softmax scale is positive, so it
       //      commutes with max and is applied inside the exponent).  Register r of a 32x32
@@ -286,8 +290,11 @@ __global__ __launch_bounds__(kAttnThreads, TG == 1 ? 1 : 2) void tree_attn_bf16_
         uint32_t pw[8];
 #pragma unroll
         for (int r = 0; r < 16; r += 2) {
-          const float p0 = fast_exp2(fmaf(s[nb][r], p.scale_log2e, neg_m));
-          const float p1 = fast_exp2(fmaf(s[nb][r + 1], p.scale_log2e, neg_m));
+          float p0 = fmaf(s[nb][r], p.scale_log2e, neg_m), p1 = fmaf(s[nb][r + 1], p.scale_log2e, neg_m);
+          if (!(PROPD_EXP & 2)) {
+            p0 = fast_exp2(p0);
+            p1 = fast_exp2(p1);
+          }
           pw[r >> 1] = cvt_pk_bf16(p0, p1);
           l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pw[r >> 1]), ones,
                                                   l_run, false);
@@ -300,7 +307,7 @@ __global__ __launch_bounds__(kAttnThreads, TG == 1 ? 1 : 2) void tree_attn_bf16_
           const int row = jb * 32 + 16 * ks2 + 4 * g + ((lane & 15) >> 2);
           const int col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
 #pragma unroll
-          for (int mb = 0; mb < 4; ++mb) {
+          for (int mb = 0; mb < ((PROPD_EXP & 4) ? 0 : 4); ++mb) {
             const uint16_t *src = &Vs[row * kVPitch + mb * 32 + col];
             const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                 (__attribute__((address_space(3))) s16x4 *)(src));
