@@ -488,39 +488,55 @@ struct PayloadArgs {
   long long stride_b[PROPD_MAX_PAYLOADS], stride_outer[PROPD_MAX_PAYLOADS],
       stride_t[PROPD_MAX_PAYLOADS];
   int vec16[PROPD_MAX_PAYLOADS];  // rows, strides and bases are all 16-byte multiples
+  long long block_end[PROPD_MAX_PAYLOADS];  // flattened grid: blocks of payloads 0..p end here
+  int slices[PROPD_MAX_PAYLOADS];           // item slices per (b, o) slot
+  int n;
 };
 
 constexpr int kGatherThreads = 256;
 
-// One workgroup per (b, o) pair of a payload (blockIdx.y selects the payload); its four
-// waves walk the survivors j = wave, wave + 4, ... and copy one row each, 16 bytes per lane.
+// Work items are (survivor row j, 16-byte piece c) pairs of one (b, o) slot of one payload.
+// The grid is flat: a block finds its payload from the per-payload block counts, then its
+// (b, o) slot and its slice of that slot's item list.  Every
+// thread moves up to kGatherItems independent pieces, so the copies of a long row (hidden
+// states) and of many short rows (tree K/V) are equally spread over the chip.
+constexpr int kGatherItems = 4;
+
 __global__ __launch_bounds__(kGatherThreads) void gather_rows_kernel(
     PayloadArgs args, int B, int T_max, const int32_t *__restrict__ orig_index,
     const int32_t *__restrict__ n_kept) {
-  const int pl = blockIdx.y;
+  int pl = 0;
+  while (pl < args.n - 1 && (long long)blockIdx.x >= args.block_end[pl]) ++pl;
+  const long long local = (long long)blockIdx.x - (pl > 0 ? args.block_end[pl - 1] : 0);
   const long long outer = args.outer[pl];
-  const long long bo = blockIdx.x;
+  const long long bo = local / args.slices[pl];
+  const unsigned slice = (unsigned)(local - bo * args.slices[pl]);
   if (bo >= (long long)B * outer) return;
   const long long o = bo % outer;
   const int b = (int)(bo / outer);
   int kept = n_kept[b];
   kept = kept > T_max ? T_max : kept;
+  const unsigned long long unit = args.vec16[pl] ? 16 : 1;  // bytes per piece
+  const unsigned long long per_row = args.row_bytes[pl] / unit;
+  const unsigned long long items = (unsigned long long)kept * per_row;
   const char *sbase = args.src[pl] + b * args.stride_b[pl] + o * args.stride_outer[pl];
   char *dbase = args.dst[pl] + b * args.stride_b[pl] + o * args.stride_outer[pl];
-  const unsigned long long nbytes = args.row_bytes[pl];
-  const int lane = threadIdx.x & 63;
-  for (int j = threadIdx.x >> 6; j < kept; j += kGatherThreads / kWave) {
+  const unsigned long long first =
+      ((unsigned long long)slice * kGatherItems) * kGatherThreads + threadIdx.x;
+#pragma unroll
+  for (int k = 0; k < kGatherItems; ++k) {
+    const unsigned long long item = first + (unsigned long long)k * kGatherThreads;
+    if (item >= items) break;
+    const int j = (int)(item / per_row);
+    const unsigned long long c = item - (unsigned long long)j * per_row;
     const int i = orig_index[(size_t)b * T_max + j];
     if (i < 0 || i >= T_max) continue;
-    const char *s = sbase + (long long)i * args.stride_t[pl];
-    char *d = dbase + (long long)j * args.stride_t[pl];
-    if (args.vec16[pl]) {
-      const unsigned long long n16 = nbytes >> 4;
-      for (unsigned long long c = lane; c < n16; c += kWave)
-        reinterpret_cast<u32x4 *>(d)[c] = reinterpret_cast<const u32x4 *>(s)[c];
-    } else {
-      for (unsigned long long c = lane; c < nbytes; c += kWave) d[c] = s[c];
-    }
+    const char *s = sbase + (long long)i * args.stride_t[pl] + c * unit;
+    char *d = dbase + (long long)j * args.stride_t[pl] + c * unit;
+    if (args.vec16[pl])
+      *reinterpret_cast<u32x4 *>(d) = *reinterpret_cast<const u32x4 *>(s);
+    else
+      *d = *s;
   }
 }
 
@@ -555,7 +571,7 @@ extern "C" propd_status propd_early_prune(
   if (dt == PROPD_BF16 && hidden % kBK != 0) return PROPD_ERR_UNSUPPORTED;
   const int B = tree->B, T_max = tree->T_max;
   if ((long long)B * T_max > (1ll << 27)) return PROPD_ERR_UNSUPPORTED;
-  long long max_rows = 0;
+  long long max_rows = 0, total_blocks = 0;
   PayloadArgs pa = {};
   for (int p = 0; p < n_payloads; ++p) {
     const propd_payload &pl = payloads[p];
@@ -573,9 +589,17 @@ extern "C" propd_status propd_early_prune(
                           (uintptr_t)pl.row_bytes | (uintptr_t)pl.stride_b |
                           (uintptr_t)pl.stride_outer | (uintptr_t)pl.stride_t;
     pa.vec16[p] = (any & 15) == 0;
-    const long long rows = (long long)B * pl.outer;  // one workgroup per (b, o)
+    const long long rows = (long long)B * pl.outer;  // grid.x: one slot per (b, o)
     if (rows > (1ll << 31) - 1) return PROPD_ERR_UNSUPPORTED;
     max_rows = rows > max_rows ? rows : max_rows;
+    const long long pieces = (long long)T_max * (long long)(pl.row_bytes / (pa.vec16[p] ? 16 : 1));
+    const long long slices = (pieces + kGatherThreads * kGatherItems - 1) /
+                             (kGatherThreads * kGatherItems);
+    if (slices > (1 << 24)) return PROPD_ERR_UNSUPPORTED;
+    pa.slices[p] = (int)slices;
+    total_blocks += rows * slices;
+    pa.block_end[p] = total_blocks;
+    if (total_blocks > (1ll << 31) - 1) return PROPD_ERR_UNSUPPORTED;
   }
   const size_t need = early_prune_workspace_bytes(B, T_max, vocab);
   if (!workspace || workspace_bytes < need) return PROPD_ERR_WORKSPACE;
@@ -631,7 +655,8 @@ extern "C" propd_status propd_early_prune(
                      tree_out->token, tree_out->depth, tree_out->anc, rank_out);
   hipLaunchKernelGGL(cu_nodes_kernel, dim3(1), dim3(kScanThreads), 0, st, B, n_kept, cu_nodes);
   if (n_payloads > 0) {
-    dim3 grid((unsigned)max_rows, (unsigned)n_payloads);
+    pa.n = n_payloads;
+    dim3 grid((unsigned)total_blocks);
     hipLaunchKernelGGL(gather_rows_kernel, grid, dim3(kGatherThreads), 0, st, pa, B, T_max,
                        orig_index, n_kept);
   }
