@@ -3,22 +3,26 @@
 //
 // bf16 path (d = 128).  The work is a stream of K/V rows from HBM that all T
 // tree queries of a (sequence, head) pair share, so the kernel is organised
-// around reading every K and V row exactly once:
-//   - a persistent grid (two workgroups of 4 waves per compute unit); the list of
-//     all K/V tiles of the call is cut into equal contiguous ranges, one per
-//     workgroup, so ragged sequence lengths balance by construction;
-//   - K/V tiles go global -> registers -> LDS, 16 bytes per lane, fully coalesced,
-//     double buffered: one barrier per tile, the tile after next in flight;
+// around reading every K and V row exactly once, as fast as HBM delivers them:
+//   - the work of a call is the list of 32-row K/V stages of all (sequence, head)
+//     units in order (cached rows, then tree rows); a persistent grid of two
+//     workgroups per compute unit cuts that list into equal contiguous ranges, so
+//     ragged sequence lengths balance by construction;
+//   - a workgroup streams its range through a ring of LDS stages with direct
+//     global->LDS loads (no registers, no LDS store instructions), issued NS-1
+//     stages ahead of the math and running straight across unit boundaries; rows
+//     are unpadded in LDS and their 16-byte chunks are XOR-swizzled by the load
+//     addresses so that both MFMA operand read patterns are bank-conflict free;
 //   - scores are computed transposed, S^T = K . Q^T, with the 32x32x16 bf16 MFMA,
 //     so that a lane owns one query column: the running max / sum of the online
 //     softmax are per-lane scalars, and the fp32 score registers, once
 //     exponentiated and rounded to bf16, ARE the B operand of the second MFMA
 //     O^T += V^T . P^T, with no shuffle or LDS round trip; V^T is read from
 //     row-major V in LDS with the transposing LDS read;
-//   - the cached prefix needs no mask; the tree part is one extra tile whose
-//     scores are kept only where the node's 128-bit ancestor set has the bit;
-//   - waves split the query columns (32 per wave) and, when the tree is small,
-//     also the rows of a tile; row groups are merged through LDS at the end;
+//   - the cached prefix needs no mask; tree stages keep a score only where the
+//     node's 128-bit ancestor set has the bit;
+//   - the four waves of a workgroup split the query columns (32 each); a wave whose
+//     columns lie beyond the tree only helps with the loads;
 //   - a unit cut by a range boundary leaves fp32 partials (O, max, sum), at most
 //     two per workgroup; a second kernel merges them.
 // fp32 path: a plain one-wave-per-query kernel, fp32 throughout.
@@ -26,28 +30,17 @@
 
 namespace propd {
 
-#ifndef PROPD_EXP
-#define PROPD_EXP 0  // timing experiments: 1 no S MFMAs, 2 no exp, 4 no PV, 8 no settle
-#endif
 constexpr int kD = 128;
 constexpr int kAttnThreads = 256;
-constexpr int kMaxGrid = 1024;  // workgroups of the persistent kernel, at most
-constexpr int kKPitch = kD + 8;   // bf16 elements per K row in LDS: 272 B, conflict-free b128 reads
-constexpr int kVPitch = kD + 32;  // bf16 elements per V row in LDS: 320 B, conflict-free transpose reads
-
-template <int TG>
-struct AttnCfg {
-  static constexpr int KG = 4 / TG;              // waves sharing one query group, splitting rows
-  static constexpr int NBW = (TG == 4) ? 2 : 1;  // 32-row blocks per wave per tile
-  static constexpr int TILE_J = 32 * KG * NBW;   // K/V rows per tile: 64, 64, 128
-  static constexpr int CH = TILE_J * 16 / kAttnThreads;  // 16-byte chunks per thread per tensor
-  static constexpr int k_elems = TILE_J * kKPitch;
-  static constexpr int v_elems = TILE_J * kVPitch;
-  static constexpr size_t buf_bytes = (size_t)(k_elems + v_elems) * 2;
-  static constexpr size_t tile_bytes = 2 * buf_bytes;  // double buffered
-  static constexpr size_t merge_bytes = (size_t)(4 - TG) * 64 * 66 * 4;  // o[64] + m + l per lane
-  static constexpr size_t lds_bytes = tile_bytes > merge_bytes ? tile_bytes : merge_bytes;
-};
+constexpr int kMaxGrid = 1024;                 // workgroups of the persistent kernel, at most
+constexpr int kStageRows = 32;                 // K/V rows per ring stage
+constexpr int kRowBytes = kD * 2;              // one bf16 row
+constexpr int kHalfStage = kStageRows * kRowBytes;  // K part of a stage; the V part follows
+constexpr int kStageBytes = 2 * kHalfStage;
+#ifndef PROPD_RING_STAGES
+#define PROPD_RING_STAGES 5
+#endif
+constexpr int kRingStages = PROPD_RING_STAGES;  // 16 KB each; two workgroups per CU share 160 KB
 
 struct AttnParams {
   const uint16_t *q, *k_cache, *v_cache, *k_tree, *v_tree;
@@ -63,6 +56,8 @@ struct AttnParams {
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((address_space(3))) void lds_void;
+typedef const __attribute__((address_space(1))) void global_void;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -72,14 +67,39 @@ __device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
 }
 
+// Transposing LDS read (ds_read_b64_tr_b16), issued as assembly so that the compiler does
+// not fence it against the ring's direct loads in flight (the builtin counts as a possible
+// LDS write, which would drain them).  The result is valid only after wait_lds<>().
+template <int OFFSET>
+__device__ __forceinline__ u32x2 lds_read_tr16(uint32_t addr) {
+  u32x2 r;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFFSET));
+  return r;
+}
+
+// wait until at most N LDS operations of this wave are outstanding; the registers named
+// are the results being waited for, so that their uses cannot be scheduled above the wait
+template <int N>
+__device__ __forceinline__ void wait_lds(u32x2 (&a)[8]) {
+  asm volatile("s_waitcnt lgkmcnt(%8)"
+               : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]),
+                 "+v"(a[7])
+               : "n"(N));
+}
+
+// wait until at most N of this wave's vector memory operations are outstanding
+template <int N>
+__device__ __forceinline__ void wait_vmem() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
 // Work decomposition shared by the main kernel and the merge kernel.  The work of one
-// call is the list of K/V tiles of all (sequence, head) units in order, each unit's
-// cached tiles followed by its tree tiles.  Workgroup w of G owns the contiguous range
+// call is the list of K/V stages of all (sequence, head) units in order, each unit's
+// cached stages followed by its tree stages.  Workgroup w of G owns the contiguous range
 // [w*N/G, (w+1)*N/G) of that list, so every workgroup streams the same number of rows
 // whatever the mix of sequence lengths; a unit cut by a range boundary is finished by
 // the merge kernel from per-workgroup partial results.
-template <int TILE_J>
-struct TileMap {
+struct StageMap {
   int B, H;
   const int32_t *seq_lens, *n_nodes;
   int L_max, T_max;
@@ -91,12 +111,16 @@ struct TileMap {
     const int T = n_nodes[b];
     return T < 1 ? 1 : (T > T_max ? T_max : T);
   }
-  __device__ __forceinline__ int cache_tiles(int b) const { return (len(b) + TILE_J - 1) / TILE_J; }
-  __device__ __forceinline__ int tree_tiles(int b) const { return (nodes(b) + TILE_J - 1) / TILE_J; }
-  __device__ __forceinline__ int unit_tiles(int b) const { return cache_tiles(b) + tree_tiles(b); }
+  __device__ __forceinline__ int cache_stages(int b) const {
+    return (len(b) + kStageRows - 1) / kStageRows;
+  }
+  __device__ __forceinline__ int tree_stages(int b) const {
+    return (nodes(b) + kStageRows - 1) / kStageRows;
+  }
+  __device__ __forceinline__ int unit_stages(int b) const { return cache_stages(b) + tree_stages(b); }
   __device__ long long total() const {
     long long n = 0;
-    for (int b = 0; b < B; ++b) n += (long long)H * unit_tiles(b);
+    for (int b = 0; b < B; ++b) n += (long long)H * unit_stages(b);
     return n;
   }
 };
@@ -105,47 +129,144 @@ __device__ __forceinline__ long long range_start(long long w, long long n, long 
   return w * n / g;
 }
 
-template <int TG>
-__global__ __launch_bounds__(kAttnThreads, TG == 1 ? 1 : 2) void tree_attn_bf16_kernel(AttnParams p) {
-  using C = AttnCfg<TG>;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  uint16_t *lds = reinterpret_cast<uint16_t *>(smem);
+// Position in the stage list: stage s of unit (b, h), with the sizes of sequence b.
+struct Cursor {
+  int b, h, s;
+  int L, T, cs, ts;  // cached rows, tree nodes, cached stages, tree stages of sequence b
+  __device__ __forceinline__ void load_sizes(const StageMap &m) {
+    L = m.len(b);
+    T = m.nodes(b);
+    cs = (L + kStageRows - 1) / kStageRows;
+    ts = (T + kStageRows - 1) / kStageRows;
+  }
+  __device__ __forceinline__ void advance(const StageMap &m, int n) {  // n <= stages left in the unit
+    s += n;
+    if (s == cs + ts) {
+      s = 0;
+      if (++h == m.H) {
+        h = 0;
+        if (b + 1 < m.B) {
+          ++b;
+          load_sizes(m);
+        }
+      }
+    }
+  }
+};
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+template <int NS>
+__global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnParams p) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_void *)smem;  // LDS byte address of the ring
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, g = lane >> 5;
-  const int tg = wave % TG, kg = wave / TG;
-  const int t = tg * 32 + l32;  // this lane's query column
+  const int t = wave * 32 + l32;  // this lane's query column
 
-  const TileMap<C::TILE_J> map = {p.B, p.H, p.seq_lens, p.n_nodes, p.L_max, p.T_max};
+  const StageMap map = {p.B, p.H, p.seq_lens, p.n_nodes, p.L_max, p.T_max};
   const long long n_total = map.total();
   const long long G = gridDim.x, w = blockIdx.x;
-  long long x = range_start(w, n_total, G);
-  const long long x_end = range_start(w + 1, n_total, G);
+  const long long x0 = range_start(w, n_total, G);
+  const int n_my = (int)(range_start(w + 1, n_total, G) - x0);
+  if (n_my <= 0) return;
 
-  int b = 0;
-  long long b_start = 0;  // first tile of sequence b in the global list
-  while (x < x_end) {
-    // ---- locate the unit that owns tile x (x only grows, so b only grows)
-    while (b < p.B - 1 && x >= b_start + (long long)p.H * map.unit_tiles(b)) {
-      b_start += (long long)p.H * map.unit_tiles(b);
-      ++b;
+  // ---- the first stage of this range
+  Cursor cp;
+  {
+    cp.b = 0;
+    long long b_start = 0;
+    while (cp.b < p.B - 1 && x0 >= b_start + (long long)p.H * map.unit_stages(cp.b)) {
+      b_start += (long long)p.H * map.unit_stages(cp.b);
+      ++cp.b;
     }
-    const int L = map.len(b), T = map.nodes(b);
-    const int ut = map.unit_tiles(b), n_cache_tiles = map.cache_tiles(b);
-    const int h = (int)((x - b_start) / ut);
-    const int tile0 = (int)((x - b_start) - (long long)h * ut);
-    const long long unit_end = b_start + (long long)(h + 1) * ut;
-    const int n_tiles = (int)((unit_end < x_end ? unit_end : x_end) - x);
-    const bool whole = tile0 == 0 && n_tiles == ut;
-    const int unit = b * p.H + h;
+    cp.load_sizes(map);
+    const int us = cp.cs + cp.ts;
+    cp.h = (int)((x0 - b_start) / us);
+    cp.s = (int)((x0 - b_start) - (long long)cp.h * us);
+  }
+  Cursor ld = cp;  // the loader runs ahead of the math over the same list
 
-    const uint16_t *kc = p.k_cache + (size_t)unit * p.L_max * kD;
-    const uint16_t *vc = p.v_cache + (size_t)unit * p.L_max * kD;
-    const uint16_t *kt = p.k_tree + (size_t)unit * p.T_max * kD;
-    const uint16_t *vt = p.v_tree + (size_t)unit * p.T_max * kD;
+  // ---- loader.  One direct load moves 64 lanes x 16 bytes = 4 rows into 1 KB of LDS that
+  //      is contiguous in lane order, so the swizzle is applied on the global side: the lane
+  //      that fills chunk c of LDS row r fetches chunk c ^ key(r) of the global row.  Keys:
+  //      K rows r & 15 (a 16-byte read of one chunk column over 16 rows touches 16 distinct
+  //      chunks); V rows ((r & 3) << 2) | ((r >> 2) & 3) (the 4 rows x 64 bytes of one
+  //      transposing read land in 4 distinct 64-byte bank groups).  A wave fills rows
+  //      4*wave + lane/16 of each 16-row half, so its keys do not depend on the half.
+  //      Rows past the last valid one re-read that last row: finite data that the mask
+  //      discards (K) or that meets a zero weight (V); padding is never touched.
+  const int ld_row = 4 * wave + (lane >> 4);
+  const int k_src_chunk = ((lane & 15) ^ ld_row) << 4;
+  const int v_src_chunk = ((lane & 15) ^ (((lane >> 4) << 2) | wave)) << 4;
+  auto issue = [&](int slot) {
+    const bool is_tree = ld.s >= ld.cs;
+    const int j0 = (is_tree ? ld.s - ld.cs : ld.s) * kStageRows;
+    const int last = (is_tree ? ld.T : ld.L) - 1;
+    const size_t unit = (size_t)ld.b * p.H + ld.h;
+    const unsigned char *kb = reinterpret_cast<const unsigned char *>(
+        is_tree ? p.k_tree + unit * p.T_max * kD : p.k_cache + unit * p.L_max * kD);
+    const unsigned char *vb = reinterpret_cast<const unsigned char *>(
+        is_tree ? p.v_tree + unit * p.T_max * kD : p.v_cache + unit * p.L_max * kD);
+    unsigned char *dst = smem + slot * kStageBytes + (4 * wave) * kRowBytes;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      int row = j0 + 16 * i + ld_row;
+      row = row > last ? last : row;
+      const size_t ro = (size_t)row * kRowBytes;
+      __builtin_amdgcn_global_load_lds((global_void *)(kb + ro + k_src_chunk),
+                                       (lds_void *)(dst + i * 16 * kRowBytes), 16, 0, 2);
+      __builtin_amdgcn_global_load_lds((global_void *)(vb + ro + v_src_chunk),
+                                       (lds_void *)(dst + kHalfStage + i * 16 * kRowBytes), 16, 0, 2);
+    }
+    ld.advance(map, 1);
+  };
+
+  // ---- per-lane LDS read offsets within a stage
+  // K as the A operand of S^T: lane = row l32, 8 consecutive d from 16*ks + 8*g (chunk 2*ks + g)
+  int k_rd[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) k_rd[ks] = l32 * kRowBytes + (((2 * ks + g) ^ (l32 & 15)) << 4);
+  // V^T as the A operand of O^T: transposing read; in each group of 16 lanes, lane i points at
+  // row i/4, 4 columns from 4*(i%4), and receives column i of those 4 rows.  Per MFMA k-step
+  // (16 rows): slots 0..3 = rows 4g + 0..3, slots 4..7 = those rows + 8.
+  int v_rd[4][2];
+#pragma unroll
+  for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+    for (int hi = 0; hi < 2; ++hi) {
+      const int r = 4 * g + ((lane & 15) >> 2) + 8 * hi;
+      const int key = ((r & 3) << 2) | ((r >> 2) & 3);
+      const int chunk = mb * 4 + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
+      v_rd[mb][hi] = kHalfStage + r * kRowBytes + ((chunk ^ key) << 4) + 8 * (lane & 1);
+    }
+
+  // ---- fill the ring
+  int slot_ld = 0;
+#pragma unroll
+  for (int s = 0; s < NS - 1; ++s)
+    if (s < n_my) {
+      issue(slot_ld);
+      slot_ld = slot_ld + 1 == NS ? 0 : slot_ld + 1;
+    }
+
+  int it = 0, slot = 0;
+  while (it < n_my) {
+    // ---- the piece of one unit that lies in this range
+    const int L = cp.L, T = cp.T, n_cache = cp.cs;
+    const int us = cp.cs + cp.ts, s0 = cp.s;
+    const int n_st = us - s0 < n_my - it ? us - s0 : n_my - it;
+    const bool whole = s0 == 0 && n_st == us;
+    const int unit = cp.b * p.H + cp.h;
+#ifdef PROPD_TIMING_NO_MATH  // timing experiment: stream only
+    const bool active = false;
+#else
+    const bool active = wave * 32 < T;  // wave-uniform: some query of this wave exists
+#endif
 
     // Q^T fragments: B operand, lane = query column, 8 consecutive d per K step
     bf16x8 qf[8];
+    uint64_t anc_lo = 0, anc_hi = 0;
     {
       const u32x4 zero4 = {0u, 0u, 0u, 0u};
       const uint16_t *qrow = p.q + ((size_t)unit * p.T_max + (t < T ? t : 0)) * kD + g * 8;
@@ -154,11 +275,15 @@ __global__ __launch_bounds__(kAttnThreads, TG == 1 ? 1 : 2) void tree_attn_bf16_
         u32x4 v = t < T ? *reinterpret_cast<const u32x4 *>(qrow + ks * 16) : zero4;
         qf[ks] = __builtin_bit_cast(bf16x8, v);
       }
-    }
-    uint64_t anc_lo = 0, anc_hi = 0;
-    if (t < T) {
-      anc_lo = p.anc[((size_t)b * p.T_max + t) * 2];
-      anc_hi = p.anc[((size_t)b * p.T_max + t) * 2 + 1];
+      if (t < T) {
+        anc_lo = p.anc[((size_t)cp.b * p.T_max + t) * 2];
+        anc_hi = p.anc[((size_t)cp.b * p.T_max + t) * 2 + 1];
+      }
+      // Touch the loaded registers here, so that the wait for them is placed before the
+      // stage loop and not inside it, where it would also drain the ring's loads in flight.
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) asm volatile("" ::"v"(qf[ks]));
+      asm volatile("" ::"v"(anc_lo), "v"(anc_hi));
     }
 
     float m_run = -INFINITY, l_run = 0.f;
@@ -168,101 +293,76 @@ __global__ __launch_bounds__(kAttnThreads, TG == 1 ? 1 : 2) void tree_attn_bf16_
 #pragma unroll
       for (int r = 0; r < 16; ++r) o_acc[mb][r] = 0.f;
 
-    // ---- tile fetch: 16-byte chunks, chunk c -> row c/16, columns (c%16)*8 .. +8
-    u32x4 k_reg[C::CH], v_reg[C::CH];
-    auto fetch = [&](int it) {
-      const int tile = tile0 + it;
-      const bool is_tree = tile >= n_cache_tiles;
-      const int j0 = (is_tree ? tile - n_cache_tiles : tile) * C::TILE_J;
-      const int rows_valid = (is_tree ? T : L) - j0;
-      const uint16_t *ksrc = (is_tree ? kt : kc) + (size_t)j0 * kD;
-      const uint16_t *vsrc = (is_tree ? vt : vc) + (size_t)j0 * kD;
-      const u32x4 zero4 = {0u, 0u, 0u, 0u};
-#pragma unroll
-      for (int i = 0; i < C::CH; ++i) {
-        const int c = i * kAttnThreads + tid;
-        const bool ok = (c >> 4) < rows_valid;  // rows beyond the valid ones read as zero
-        k_reg[i] = ok ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(ksrc) + c) : zero4;
-        v_reg[i] = ok ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(vsrc) + c) : zero4;
+    for (int i = 0; i < n_st; ++i, ++it) {
+      // stage `it` has landed once at most the loads of the NS-2 stages issued after it
+      // (4 per wave and stage) are outstanding; near the end of the range fewer follow it
+      if (it + NS - 2 <= n_my - 1) wait_vmem<4 * (NS - 2)>(); else wait_vmem<0>();
+      __builtin_amdgcn_s_barrier();  // stage `it` is visible; every wave is done with stage it-1
+#ifdef PROPD_TIMING_NO_LOADS  // timing experiment: math on whatever the ring holds
+      if (false) {
+#else
+      if (it + NS - 1 < n_my) {
+#endif
+        issue(slot_ld);  // refill the slot of stage it-1
+        slot_ld = slot_ld + 1 == NS ? 0 : slot_ld + 1;
       }
-    };
-    auto stash = [&](int buf) {
-      uint16_t *Ks = lds + buf * (C::k_elems + C::v_elems);
-      uint16_t *Vs = Ks + C::k_elems;
-#pragma unroll
-      for (int i = 0; i < C::CH; ++i) {
-        const int c = i * kAttnThreads + tid;
-        const int row = c >> 4, col = (c & 15) * 8;
-        *reinterpret_cast<u32x4 *>(&Ks[row * kKPitch + col]) = k_reg[i];
-        *reinterpret_cast<u32x4 *>(&Vs[row * kVPitch + col]) = v_reg[i];
-      }
-    };
+      const unsigned char *st = smem + slot * kStageBytes;
+      slot = slot + 1 == NS ? 0 : slot + 1;
 
-    fetch(0);
-    stash(0);
-    if (n_tiles > 1) fetch(1);
-    __syncthreads();
-
-    for (int it = 0; it < n_tiles; ++it) {
-      const int cur = it & 1;
-      // tile it+1 is in registers: park it in the other buffer (free since the last
-      // barrier), then start loading tile it+2; both overlap with the math below
-      if (it + 1 < n_tiles) stash(cur ^ 1);
-      if (it + 2 < n_tiles) fetch(it + 2);
-
-      const uint16_t *Ks = lds + cur * (C::k_elems + C::v_elems);
-      const uint16_t *Vs = Ks + C::k_elems;
-      const int tile = tile0 + it;
-      const bool is_tree = tile >= n_cache_tiles;
-      const int j0 = (is_tree ? tile - n_cache_tiles : tile) * C::TILE_J;
+      const int s = s0 + i;
+      const bool is_tree = s >= n_cache;
+      const int j0 = (is_tree ? s - n_cache : s) * kStageRows;
+      // tree rows after this wave's last query are descendants or strangers of all its queries
+      if (!active || (is_tree && j0 > wave * 32 + 31)) continue;
       int n_valid = (is_tree ? T : L) - j0;
-      n_valid = n_valid > C::TILE_J ? C::TILE_J : n_valid;
-      const bool partial = is_tree || n_valid < C::TILE_J;  // uniform over the workgroup
+      n_valid = n_valid > kStageRows ? kStageRows : n_valid;
+      const bool partial = is_tree || n_valid < kStageRows;  // uniform over the workgroup
 
-      // ---- S^T = K . Q^T for this wave's row blocks
-      f32x16 s[C::NBW];
+      // ---- S^T = K . Q^T
+      f32x16 sc;
 #pragma unroll
-      for (int nb = 0; nb < C::NBW; ++nb) {
-        const int jb = kg * C::NBW + nb;
+      for (int r = 0; r < 16; ++r) sc[r] = 0.f;
 #pragma unroll
-        for (int r = 0; r < 16; ++r)
-          s[nb][r] = (PROPD_EXP & 1) ? (float)__builtin_bit_cast(u32x4, qf[r & 7]).x * 1e-12f : 0.f;
+      for (int ks = 0; ks < 8; ++ks) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(st + k_rd[ks]);
+        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], sc, 0, 0, 0);
+      }
+      mfma_settle();
+
+      // ---- start the transposing reads of the whole V stage now; they complete while the
+      //      softmax below runs.  vt[ks2][2*mb + hi]: k-step ks2 (16 rows), d block mb.
+      u32x2 vt[2][8];
+      {
+        const uint32_t vs = smem_base + (uint32_t)(st - smem);
 #pragma unroll
-        for (int ks = 0; ks < ((PROPD_EXP & 1) ? 0 : 8); ++ks) {
-          const bf16x8 a =
-              *reinterpret_cast<const bf16x8 *>(&Ks[(jb * 32 + l32) * kKPitch + ks * 16 + g * 8]);
-          s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[nb], 0, 0, 0);
+        for (int mb = 0; mb < 4; ++mb) {
+          vt[0][2 * mb] = lds_read_tr16<0>(vs + v_rd[mb][0]);
+          vt[0][2 * mb + 1] = lds_read_tr16<0>(vs + v_rd[mb][1]);
+        }
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb) {
+          vt[1][2 * mb] = lds_read_tr16<16 * kRowBytes>(vs + v_rd[mb][0]);
+          vt[1][2 * mb + 1] = lds_read_tr16<16 * kRowBytes>(vs + v_rd[mb][1]);
         }
       }
-      if (!(PROPD_EXP & 8)) mfma_settle();
 
       // ---- mask and running max on the raw scores (the softmax scale is positive, so it
       //      commutes with max and is applied inside the exponent).  Register r of a 32x32
-      //      accumulator holds row 8*(r/4) + 4*g + r%4 of the block, i.e. K/V row j of the tile.
+      //      accumulator holds row 8*(r/4) + 4*g + r%4 of the block, i.e. K/V row j0 + that.
       if (partial) {
-        // tile-local visibility of this lane's query: cached rows below L for every
+        // visibility of the stage's rows to this lane's query: cached rows below L for every
         // query, tree rows only where the node's ancestor set has the bit
-        uint64_t vis_lo, vis_hi;
-        mask_below(n_valid, vis_lo, vis_hi);
-        const uint64_t t_lo = j0 >= 64 ? anc_hi : anc_lo;  // tree tiles start at row 0 or 64
-        const uint64_t t_hi = j0 >= 64 ? 0ull : anc_hi;
-        vis_lo &= is_tree ? t_lo : ~0ull;
-        vis_hi &= is_tree ? t_hi : ~0ull;
+        uint32_t vis = n_valid >= 32 ? ~0u : ((1u << n_valid) - 1u);
+        const uint64_t word = j0 >= 64 ? anc_hi : anc_lo;  // tree stages start at 0, 32, 64, 96
+        vis &= is_tree ? (uint32_t)(word >> (j0 & 32)) : ~0u;
+        vis >>= 4 * g;
 #pragma unroll
-        for (int nb = 0; nb < C::NBW; ++nb) {
-          const int jb = kg * C::NBW + nb;
-          const uint64_t word = (jb & 2) ? vis_hi : vis_lo;
-          const uint32_t vis = (uint32_t)(word >> ((jb & 1) * 32)) >> (4 * g);
-#pragma unroll
-          for (int r = 0; r < 16; ++r)
-            s[nb][r] = ((vis >> (8 * (r >> 2) + (r & 3))) & 1u) ? s[nb][r] : -INFINITY;
-        }
+        for (int r = 0; r < 16; ++r)
+          sc[r] = ((vis >> (8 * (r >> 2) + (r & 3))) & 1u) ? sc[r] : -INFINITY;
       }
       float m_blk = -INFINITY;
 #pragma unroll
-      for (int nb = 0; nb < C::NBW; ++nb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) m_blk = fmaxf(m_blk, s[nb][r]);
+      for (int r = 0; r < 16; ++r) m_blk = fmaxf(m_blk, sc[r]);
       m_blk = fmaxf(m_blk, __shfl_xor(m_blk, 32, kWave));
       const float m_new = fmaxf(m_run, m_blk);
       const float m_safe = m_new == -INFINITY ? 0.f : m_new;
@@ -278,89 +378,39 @@ __global__ __launch_bounds__(kAttnThreads, TG == 1 ? 1 : 2) void tree_attn_bf16_
       }
       const float neg_m = -m_safe * p.scale_log2e;
 
-      // ---- P^T (bf16) straight from the score registers, then O^T += V^T . P^T.
-      //      The A operand V^T comes from row-major V in LDS through the transposing
-      //      read: in each group of 16 lanes, lane i points at row i/4, 4 columns from
-      //      4*(i%4), and receives column i of those 4 rows.  The row sums are taken over
-      //      the rounded bf16 weights, the same values the MFMA multiplies.
+      // ---- P^T (bf16) straight from the score registers, then O^T += V^T . P^T.  The row
+      //      sums are taken over the rounded bf16 weights, the same values the MFMA multiplies.
       const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3f803f80u);
+      uint32_t pw[8];
 #pragma unroll
-      for (int nb = 0; nb < C::NBW; ++nb) {
-        const int jb = kg * C::NBW + nb;
-        uint32_t pw[8];
+      for (int r = 0; r < 16; r += 2) {
+        const float p0 = fast_exp2(fmaf(sc[r], p.scale_log2e, neg_m));
+        const float p1 = fast_exp2(fmaf(sc[r + 1], p.scale_log2e, neg_m));
+        pw[r >> 1] = cvt_pk_bf16(p0, p1);
+        l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pw[r >> 1]), ones, l_run,
+                                                false);
+      }
+      wait_lds<8>(vt[0]);  // LDS reads return in order: the first eight are in
 #pragma unroll
-        for (int r = 0; r < 16; r += 2) {
-          float p0 = fmaf(s[nb][r], p.scale_log2e, neg_m), p1 = fmaf(s[nb][r + 1], p.scale_log2e, neg_m);
-          if (!(PROPD_EXP & 2)) {
-            p0 = fast_exp2(p0);
-            p1 = fast_exp2(p1);
-          }
-          pw[r >> 1] = cvt_pk_bf16(p0, p1);
-          l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pw[r >> 1]), ones,
-                                                  l_run, false);
-        }
+      for (int ks2 = 0; ks2 < 2; ++ks2) {
+        if (ks2 == 1) wait_lds<0>(vt[1]);
+        const u32x4 pv = {pw[4 * ks2], pw[4 * ks2 + 1], pw[4 * ks2 + 2], pw[4 * ks2 + 3]};
+        const bf16x8 pf = __builtin_bit_cast(bf16x8, pv);
 #pragma unroll
-        for (int ks2 = 0; ks2 < 2; ++ks2) {
-          const u32x4 pv = {pw[4 * ks2], pw[4 * ks2 + 1], pw[4 * ks2 + 2], pw[4 * ks2 + 3]};
-          const bf16x8 pf = __builtin_bit_cast(bf16x8, pv);
-          // slots 0..3: rows 16*ks2 + 4g + 0..3; slots 4..7: those rows + 8
-          const int row = jb * 32 + 16 * ks2 + 4 * g + ((lane & 15) >> 2);
-          const int col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-#pragma unroll
-          for (int mb = 0; mb < ((PROPD_EXP & 4) ? 0 : 4); ++mb) {
-            const uint16_t *src = &Vs[row * kVPitch + mb * 32 + col];
-            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (__attribute__((address_space(3))) s16x4 *)(src));
-            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (__attribute__((address_space(3))) s16x4 *)(src + 8 * kVPitch));
-            const u32x2 lo2 = __builtin_bit_cast(u32x2, lo), hi2 = __builtin_bit_cast(u32x2, hi);
-            const u32x4 aw = {lo2.x, lo2.y, hi2.x, hi2.y};
-            o_acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, aw), pf,
-                                                                o_acc[mb], 0, 0, 0);
-          }
+        for (int mb = 0; mb < 4; ++mb) {
+          const u32x4 aw = {vt[ks2][2 * mb].x, vt[ks2][2 * mb].y, vt[ks2][2 * mb + 1].x,
+                            vt[ks2][2 * mb + 1].y};
+          o_acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, aw), pf,
+                                                              o_acc[mb], 0, 0, 0);
         }
       }
-      __syncthreads();  // tile it is consumed, tile it+1 is visible
-    }
-
-    // ---- merge the row groups of one query group through LDS (lane-wise)
-    mfma_settle();
-    l_run += __shfl_xor(l_run, 32, kWave);
-    m_run *= p.scale_log2e;  // from here on the maximum is in the exponent's (log2) domain
-    if (C::KG > 1) {
-      float *mg = reinterpret_cast<float *>(smem);
-      if (kg > 0) {
-        float *slot = mg + (size_t)((kg - 1) * TG + tg) * 66 * 64;
-#pragma unroll
-        for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) slot[(mb * 16 + r) * 64 + lane] = o_acc[mb][r];
-        slot[64 * 64 + lane] = m_run;
-        slot[65 * 64 + lane] = l_run;
-      }
-      __syncthreads();
-      if (kg == 0) {
-#pragma unroll
-        for (int k2 = 1; k2 < C::KG; ++k2) {
-          const float *slot = mg + (size_t)((k2 - 1) * TG + tg) * 66 * 64;
-          const float m2 = slot[64 * 64 + lane], l2 = slot[65 * 64 + lane];
-          const float m_new = fmaxf(m_run, m2);
-          const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-          const float a1 = fast_exp2(m_run - m_safe), a2 = fast_exp2(m2 - m_safe);
-          l_run = l_run * a1 + l2 * a2;
-          m_run = m_new;
-#pragma unroll
-          for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-              o_acc[mb][r] = o_acc[mb][r] * a1 + slot[(mb * 16 + r) * 64 + lane] * a2;
-        }
-      }
-      __syncthreads();  // the buffers are reused by the next segment
     }
 
     // ---- write: lane holds d = mb*32 + 8*(r/4) + 4*g + r%4 for its query t
-    if (kg == 0 && t < T) {
+    mfma_settle();
+    l_run += __shfl_xor(l_run, 32, kWave);
+    m_run *= p.scale_log2e;  // from here on the maximum is in the exponent's (log2) domain
+    if (t < T) {
       if (whole) {
         const float inv = 1.f / l_run;
         uint16_t *orow = p.out + ((size_t)unit * p.T_max + t) * kD;
@@ -375,8 +425,8 @@ __global__ __launch_bounds__(kAttnThreads, TG == 1 ? 1 : 2) void tree_attn_bf16_
           }
       } else {
         // a range starts inside at most one unit and ends inside at most one
-        const size_t slot = 2 * (size_t)w + (tile0 > 0 ? 0 : 1);
-        float *po = p.part_o + (slot * 128 + t) * kD;
+        const size_t ps = 2 * (size_t)w + (s0 > 0 ? 0 : 1);
+        float *po = p.part_o + (ps * 128 + t) * kD;
 #pragma unroll
         for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
@@ -386,28 +436,27 @@ __global__ __launch_bounds__(kAttnThreads, TG == 1 ? 1 : 2) void tree_attn_bf16_
             *reinterpret_cast<f32x4 *>(po + mb * 32 + 8 * q4 + 4 * g) = w4;
           }
         if (g == 0) {
-          p.part_ml[(slot * 128 + t) * 2] = m_run;
-          p.part_ml[(slot * 128 + t) * 2 + 1] = l_run;
+          p.part_ml[(ps * 128 + t) * 2] = m_run;
+          p.part_ml[(ps * 128 + t) * 2 + 1] = l_run;
         }
       }
     }
-    x += n_tiles;
+    cp.advance(map, n_st);
   }
 }
 
 // Finish the units that a range boundary cut: out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s
 // over the workgroups s that hold a piece.  One workgroup per unit; whole units return at once.
-template <int TILE_J>
 __global__ __launch_bounds__(kAttnThreads) void tree_attn_combine_kernel(AttnParams p, int G) {
   const int unit = blockIdx.x;
   const int b = unit / p.H, h = unit - b * p.H;
-  const TileMap<TILE_J> map = {p.B, p.H, p.seq_lens, p.n_nodes, p.L_max, p.T_max};
+  const StageMap map = {p.B, p.H, p.seq_lens, p.n_nodes, p.L_max, p.T_max};
   long long n_total = 0, b_start = 0;
   for (int bb = 0; bb < p.B; ++bb) {
     if (bb == b) b_start = n_total;
-    n_total += (long long)p.H * map.unit_tiles(bb);
+    n_total += (long long)p.H * map.unit_stages(bb);
   }
-  const int ut = map.unit_tiles(b), T = map.nodes(b);
+  const int ut = map.unit_stages(b), T = map.nodes(b);
   const long long S = b_start + (long long)h * ut, E = S + ut;
   // workgroup that owns tile x: the largest w with range_start(w) <= x
   auto owner = [&](long long x) {
@@ -520,10 +569,6 @@ __global__ __launch_bounds__(kWave) void tree_attn_f32_kernel(AttnParamsF32 p) {
 // ------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------
-static int pick_tg(int T_max) { return T_max <= 32 ? 1 : (T_max <= 64 ? 2 : 4); }
-
-static int tile_rows(int tg) { return tg == 1 ? AttnCfg<1>::TILE_J : AttnCfg<4>::TILE_J; }
-
 static int compute_units() {
   static int cus = 0;
   if (cus == 0) {
@@ -536,15 +581,14 @@ static int compute_units() {
   return cus;
 }
 
-// Workgroups of the persistent kernel: two per compute unit (what LDS and registers
-// allow to be resident), fewer when the whole call has fewer than two tiles per workgroup.
+// Workgroups of the persistent kernel: two per compute unit (what LDS allows to be
+// resident), fewer when the whole call has fewer than two stages per workgroup.
 static int pick_grid(int B, int H, int L_max, int T_max) {
-  const int tile = tile_rows(pick_tg(T_max));
-  const long long per_unit = (L_max + tile - 1) / tile + (T_max + tile - 1) / tile;
-  const long long tiles = (long long)B * H * per_unit;
+  const long long per_unit = (L_max + kStageRows - 1) / kStageRows + (T_max + kStageRows - 1) / kStageRows;
+  const long long stages = (long long)B * H * per_unit;
   long long grid = 2ll * compute_units();
   if (grid > kMaxGrid) grid = kMaxGrid;
-  if (grid > (tiles + 1) / 2) grid = (tiles + 1) / 2;
+  if (grid > (stages + 1) / 2) grid = (stages + 1) / 2;
   return (int)(grid < 1 ? 1 : grid);
 }
 
@@ -554,21 +598,20 @@ size_t tree_attention_workspace_bytes(int B, int H, int L_max, int T_max) {
   return align_up(slots * 128 * kD * 4, 256) + align_up(slots * 128 * 2 * 4, 256);
 }
 
-template <int TG>
 static bool launch_bf16(const AttnParams &p, int grid, int units, hipStream_t st) {
+  constexpr int lds_bytes = kRingStages * kStageBytes;
   static bool attr_set = false;
   if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_attn_bf16_kernel<TG>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)AttnCfg<TG>::lds_bytes) != hipSuccess)
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_attn_bf16_kernel<kRingStages>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess)
       return false;
     attr_set = true;
   }
-  hipLaunchKernelGGL(tree_attn_bf16_kernel<TG>, dim3((unsigned)grid), dim3(kAttnThreads),
-                     AttnCfg<TG>::lds_bytes, st, p);
+  hipLaunchKernelGGL(tree_attn_bf16_kernel<kRingStages>, dim3((unsigned)grid), dim3(kAttnThreads),
+                     lds_bytes, st, p);
   if (!launch_ok()) return false;
-  hipLaunchKernelGGL(tree_attn_combine_kernel<AttnCfg<TG>::TILE_J>, dim3((unsigned)units),
-                     dim3(kAttnThreads), 0, st, p, grid);
+  hipLaunchKernelGGL(tree_attn_combine_kernel, dim3((unsigned)units), dim3(kAttnThreads), 0, st, p,
+                     grid);
   return launch_ok();
 }
 
@@ -637,13 +680,7 @@ extern "C" propd_status propd_tree_attention(const propd_tree *tree, propd_dtype
   p.part_o = reinterpret_cast<float *>(workspace);
   p.part_ml = reinterpret_cast<float *>(reinterpret_cast<char *>(workspace) +
                                         align_up(slots * 128 * kD * 4, 256));
-  bool ok;
-  switch (pick_tg(tree->T_max)) {
-    case 1: ok = launch_bf16<1>(p, grid, (int)units, st); break;
-    case 2: ok = launch_bf16<2>(p, grid, (int)units, st); break;
-    default: ok = launch_bf16<4>(p, grid, (int)units, st); break;
-  }
-  if (!ok) return PROPD_ERR_DEVICE;
+  if (!launch_bf16(p, grid, (int)units, st)) return PROPD_ERR_DEVICE;
   return PROPD_OK;
 }
 
