@@ -26,6 +26,8 @@
 //   - a unit cut by a range boundary leaves fp32 partials (O, max, sum), at most
 //     two per workgroup; a second kernel merges them.
 // fp32 path: a plain one-wave-per-query kernel, fp32 throughout.
+#include <type_traits>
+
 #include "common.h"
 
 namespace propd {
@@ -93,6 +95,82 @@ __device__ __forceinline__ void wait_vmem() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
+// Global loads and stores issued as assembly.  The main kernel keeps its own count of
+// the vector memory operations in flight (they complete in issue order), so that it can
+// wait for a ring stage without also waiting for output stores issued after it; the
+// compiler's own bookkeeping would fence every one of them.  The compiler's hazard
+// recognizer does not look inside assembly either: the stores carry their own wait states
+// for data registers written just before by vector or cross-lane instructions, and after
+// themselves, because a store wider than 8 bytes still reads its data registers when the
+// next instruction issues.
+__device__ __forceinline__ u32x4 global_load16_untracked(const void *ptr) {
+  u32x4 r;
+  asm volatile("s_nop 3\n\tglobal_load_dwordx4 %0, %1, off" : "=v"(r) : "v"(ptr) : "memory");
+  return r;
+}
+__device__ __forceinline__ void global_store16_untracked(void *ptr, u32x4 v) {
+  asm volatile("s_nop 7\n\tglobal_store_dwordx4 %0, %1, off sc1\n\ts_nop 3" ::"v"(ptr), "v"(v) : "memory");
+}
+__device__ __forceinline__ void global_store4_untracked(void *ptr, float v) {
+  asm volatile("s_nop 7\n\tglobal_store_dword %0, %1, off sc1\n\ts_nop 3" ::"v"(ptr), "v"(v) : "memory");
+}
+
+// wait until at most n of this wave's vector memory operations are outstanding, for a
+// wave-uniform n known only at run time: the largest immediate of the ladder that is <= n
+__device__ __forceinline__ void wait_vmem_upto(int n) {
+  if (n == 4) wait_vmem<4>();
+  else if (n >= 31) wait_vmem<31>();
+  else if (n >= 22) wait_vmem<22>();
+  else if (n >= 21) wait_vmem<21>();
+  else if (n >= 13) wait_vmem<13>();
+  else if (n >= 12) wait_vmem<12>();
+  else if (n >= 8) wait_vmem<8>();
+  else if (n >= 4) wait_vmem<4>();
+  else wait_vmem<0>();
+}
+
+// Exchange between the two 32-lane halves of a wave (v_permlane32_swap): afterwards lane
+// l < 32 holds (a[l], a[l+32]) and lane l >= 32 holds (b[l-32], b[l]) in (a, b).
+__device__ __forceinline__ void swap_halves(uint32_t &a, uint32_t &b) {
+  const auto r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
+  a = r[0];
+  b = r[1];
+}
+
+// A lane of the main kernel holds, for its query t = 32*wave + lane%32, the 64 values
+// d = 32*mb + 8*q4 + 4*(lane/32) + j of O^T in o_acc[mb][4*q4 + j].
+// Output rows: neighbouring q4 of the two lane halves are exchanged so that every lane
+// writes 8 consecutive bf16 values (16 bytes) per store.
+template <bool kUntracked>
+__device__ __forceinline__ void store_out_row(uint16_t *orow, const f32x16 (&o)[4], float inv, int g) {
+#pragma unroll
+  for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+    for (int jp = 0; jp < 2; ++jp) {
+      const int e = 8 * jp, od = 8 * jp + 4;  // first register of the even / odd q4 of the pair
+      uint32_t a0 = cvt_pk_bf16(o[mb][e] * inv, o[mb][e + 1] * inv);
+      uint32_t a1 = cvt_pk_bf16(o[mb][e + 2] * inv, o[mb][e + 3] * inv);
+      uint32_t b0 = cvt_pk_bf16(o[mb][od] * inv, o[mb][od + 1] * inv);
+      uint32_t b1 = cvt_pk_bf16(o[mb][od + 2] * inv, o[mb][od + 3] * inv);
+      swap_halves(a0, b0);
+      swap_halves(a1, b1);
+      // lower half: d = 32*mb + 16*jp + 0..7, upper half: the 8 values after those
+      const u32x4 w4 = {a0, a1, b0, b1};
+      if (kUntracked) global_store16_untracked(orow + mb * 32 + 16 * jp + 8 * g, w4);
+      else *reinterpret_cast<u32x4 *>(orow + mb * 32 + 16 * jp + 8 * g) = w4;
+    }
+}
+constexpr int kOutRowStores = 8;  // stores per lane of store_out_row
+
+// Partial results keep the register layout, so that a wave writes and reads them as
+// contiguous 1 KB blocks: part_o[slot][wave][4*mb + q4][lane][j], part_ml[slot][wave][m|l][lane].
+__device__ __forceinline__ size_t part_o_index(size_t slot, int wave, int blk, int lane) {
+  return (((slot * 4 + wave) * 16 + blk) * 64 + lane) * 4;
+}
+__device__ __forceinline__ size_t part_ml_index(size_t slot, int wave, int which, int lane) {
+  return ((slot * 4 + wave) * 2 + which) * 64 + lane;
+}
+
 // Work decomposition shared by the main kernel and the merge kernel.  The work of one
 // call is the list of K/V stages of all (sequence, head) units in order, each unit's
 // cached stages followed by its tree stages.  Workgroup w of G owns the contiguous range
@@ -156,6 +234,8 @@ struct Cursor {
 
 template <int NS>
 __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnParams p) {
+  static_assert(NS >= 4, "three stages are in use by the math, the rest is in flight");
+  constexpr int kAhead = NS - 3;  // stages in flight beyond the newest one the math uses
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_void *)smem;  // LDS byte address of the ring
 
@@ -185,52 +265,86 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnPar
     cp.h = (int)((x0 - b_start) / us);
     cp.s = (int)((x0 - b_start) - (long long)cp.h * us);
   }
-  Cursor ld = cp;  // the loader runs ahead of the math over the same list
 
-  // ---- loader.  One direct load moves 64 lanes x 16 bytes = 4 rows into 1 KB of LDS that
-  //      is contiguous in lane order, so the swizzle is applied on the global side: the lane
-  //      that fills chunk c of LDS row r fetches chunk c ^ key(r) of the global row.  Keys:
-  //      K rows r & 15 (a 16-byte read of one chunk column over 16 rows touches 16 distinct
-  //      chunks); V rows ((r & 3) << 2) | ((r >> 2) & 3) (the 4 rows x 64 bytes of one
-  //      transposing read land in 4 distinct 64-byte bank groups).  A wave fills rows
-  //      4*wave + lane/16 of each 16-row half, so its keys do not depend on the half.
-  //      Rows past the last valid one re-read that last row: finite data that the mask
-  //      discards (K) or that meets a zero weight (V); padding is never touched.
+  // ---- loader.  It walks the same stage list ahead of the math, one segment (the cached
+  //      rows or the tree rows of a unit) at a time.  One direct load moves 64 lanes x 16
+  //      bytes = 4 rows into 1 KB of LDS that is contiguous in lane order, so the swizzle is
+  //      applied on the global side: the lane that fills chunk c of LDS row r fetches chunk
+  //      c ^ key(r) of the global row.  Keys: K rows r & 15 (a 16-byte read of one chunk
+  //      column over 16 rows touches 16 distinct chunks); V rows ((r & 3) << 2) | ((r >> 2) & 3)
+  //      (the 4 rows x 64 bytes of one transposing read land in 4 distinct 64-byte bank
+  //      groups).  A wave fills rows 4*wave + lane/16 of each 16-row half, so its keys do not
+  //      depend on the half.  Rows past the last valid one of a segment re-read that last
+  //      row: finite data that the mask discards (K) or that meets a zero weight (V);
+  //      padding is never touched.
   const int ld_row = 4 * wave + (lane >> 4);
-  const int k_src_chunk = ((lane & 15) ^ ld_row) << 4;
-  const int v_src_chunk = ((lane & 15) ^ (((lane >> 4) << 2) | wave)) << 4;
+  const int k_lane_chunk = ((lane & 15) ^ ld_row) << 4;
+  const int v_lane_chunk = ((lane & 15) ^ (((lane >> 4) << 2) | wave)) << 4;
+  int ld_b = cp.b, ld_h = cp.h, ld_L = cp.L, ld_T = cp.T;
+  bool ld_tree;
+  int ld_rows;                       // rows left in the segment, from the next stage to issue
+  const unsigned char *ld_k, *ld_v;  // first row of the next stage to issue
+  auto ld_segment = [&](bool tree, int first_row) {
+    const size_t unit = (size_t)ld_b * p.H + ld_h;
+    ld_tree = tree;
+    ld_rows = (tree ? ld_T : ld_L) - first_row;
+    const size_t row0 = (tree ? unit * p.T_max : unit * p.L_max) + first_row;
+    ld_k = reinterpret_cast<const unsigned char *>(tree ? p.k_tree : p.k_cache) + row0 * kRowBytes;
+    ld_v = reinterpret_cast<const unsigned char *>(tree ? p.v_tree : p.v_cache) + row0 * kRowBytes;
+  };
+  if (cp.s < cp.cs) ld_segment(false, cp.s * kStageRows);
+  else ld_segment(true, (cp.s - cp.cs) * kStageRows);
+  auto dma16 = [&](const unsigned char *src, unsigned char *dst) {
+    __builtin_amdgcn_global_load_lds((global_void *)src, (lds_void *)dst, 16, 0, 2 /* nt */);
+  };
   auto issue = [&](int slot) {
-    const bool is_tree = ld.s >= ld.cs;
-    const int j0 = (is_tree ? ld.s - ld.cs : ld.s) * kStageRows;
-    const int last = (is_tree ? ld.T : ld.L) - 1;
-    const size_t unit = (size_t)ld.b * p.H + ld.h;
-    const unsigned char *kb = reinterpret_cast<const unsigned char *>(
-        is_tree ? p.k_tree + unit * p.T_max * kD : p.k_cache + unit * p.L_max * kD);
-    const unsigned char *vb = reinterpret_cast<const unsigned char *>(
-        is_tree ? p.v_tree + unit * p.T_max * kD : p.v_cache + unit * p.L_max * kD);
     unsigned char *dst = smem + slot * kStageBytes + (4 * wave) * kRowBytes;
+    if (ld_rows >= kStageRows) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      int row = j0 + 16 * i + ld_row;
-      row = row > last ? last : row;
-      const size_t ro = (size_t)row * kRowBytes;
-      __builtin_amdgcn_global_load_lds((global_void *)(kb + ro + k_src_chunk),
-                                       (lds_void *)(dst + i * 16 * kRowBytes), 16, 0, 2);
-      __builtin_amdgcn_global_load_lds((global_void *)(vb + ro + v_src_chunk),
-                                       (lds_void *)(dst + kHalfStage + i * 16 * kRowBytes), 16, 0, 2);
+      for (int i = 0; i < 2; ++i) {
+        const int ro = (16 * i + ld_row) * kRowBytes;
+        dma16(ld_k + (ro + k_lane_chunk), dst + i * 16 * kRowBytes);
+        dma16(ld_v + (ro + v_lane_chunk), dst + kHalfStage + i * 16 * kRowBytes);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        int row = 16 * i + ld_row;
+        row = row < ld_rows ? row : ld_rows - 1;
+        dma16(ld_k + (row * kRowBytes + k_lane_chunk), dst + i * 16 * kRowBytes);
+        dma16(ld_v + (row * kRowBytes + v_lane_chunk), dst + kHalfStage + i * 16 * kRowBytes);
+      }
     }
-    ld.advance(map, 1);
+    ld_rows -= kStageRows;
+    ld_k += kHalfStage;
+    ld_v += kHalfStage;
+    if (ld_rows <= 0) {
+      if (!ld_tree) {
+        ld_segment(true, 0);
+      } else {
+        if (++ld_h == p.H) {
+          ld_h = 0;
+          if (ld_b + 1 < p.B) {
+            ++ld_b;
+            ld_L = map.len(ld_b);
+            ld_T = map.nodes(ld_b);
+          }
+        }
+        ld_segment(ld_L == 0, 0);
+      }
+    }
   };
 
   // ---- per-lane LDS read offsets within a stage
   // K as the A operand of S^T: lane = row l32, 8 consecutive d from 16*ks + 8*g (chunk 2*ks + g)
-  int k_rd[8];
+  uint32_t k_rd[8];
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) k_rd[ks] = l32 * kRowBytes + (((2 * ks + g) ^ (l32 & 15)) << 4);
+  for (int ks = 0; ks < 8; ++ks)
+    k_rd[ks] = smem_base + l32 * kRowBytes + (((2 * ks + g) ^ (l32 & 15)) << 4);
   // V^T as the A operand of O^T: transposing read; in each group of 16 lanes, lane i points at
   // row i/4, 4 columns from 4*(i%4), and receives column i of those 4 rows.  Per MFMA k-step
   // (16 rows): slots 0..3 = rows 4g + 0..3, slots 4..7 = those rows + 8.
-  int v_rd[4][2];
+  uint32_t v_rd[4][2];
 #pragma unroll
   for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
@@ -238,215 +352,322 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnPar
       const int r = 4 * g + ((lane & 15) >> 2) + 8 * hi;
       const int key = ((r & 3) << 2) | ((r >> 2) & 3);
       const int chunk = mb * 4 + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
-      v_rd[mb][hi] = kHalfStage + r * kRowBytes + ((chunk ^ key) << 4) + 8 * (lane & 1);
+      v_rd[mb][hi] = smem_base + kHalfStage + r * kRowBytes + ((chunk ^ key) << 4) + 8 * (lane & 1);
     }
 
-  // ---- fill the ring
-  int slot_ld = 0;
+  // ---- ring bookkeeping.  acquire() is called once per stage of the range, in order, by
+  //      every wave: it waits for the stage's loads, meets the other waves, and refills the
+  //      slot whose stage every wave finished two acquires ago.  Vector memory operations
+  //      of a wave complete in issue order, so "stage x has landed" is "at most N operations
+  //      outstanding" with N = the number issued after the loads of stage x: those of stage
+  //      x+1, and whatever else (query loads, output stores: vm_a since the last acquire,
+  //      vm_b between the two before) the wave has issued since.
+  static_assert(kAhead == 2, "the operation count below covers the last two acquires");
+  int n_acq = 0;              // stages acquired so far
+  int slot_acq = 0;           // slot of the next stage to acquire
+  int slot_ld = 0;            // slot of the next stage to issue
+  int vm_a = 0, vm_b = 0;     // other vector memory operations issued, see above
+  int q_after = 0;            // operations issued after the pending query loads
+  auto next_slot = [](int sl) { return sl + 1 == NS ? 0 : sl + 1; };
 #pragma unroll
-  for (int s = 0; s < NS - 1; ++s)
-    if (s < n_my) {
+  for (int i = 0; i < kAhead; ++i)
+    if (i < n_my) {
       issue(slot_ld);
-      slot_ld = slot_ld + 1 == NS ? 0 : slot_ld + 1;
+      slot_ld = next_slot(slot_ld);
     }
+  auto acquire = [&]() -> int {
+    if (n_acq + 1 < n_my) wait_vmem_upto(4 + vm_a + vm_b); else wait_vmem<0>();
+    __builtin_amdgcn_s_barrier();
+    if (n_acq + kAhead < n_my) {
+      issue(slot_ld);
+      slot_ld = next_slot(slot_ld);
+      q_after += 4;
+    }
+    vm_b = vm_a;
+    vm_a = 0;
+    const int sl = slot_acq;
+    slot_acq = next_slot(slot_acq);
+    ++n_acq;
+    return sl;
+  };
 
-  int it = 0, slot = 0;
-  while (it < n_my) {
-    // ---- the piece of one unit that lies in this range
-    const int L = cp.L, T = cp.T, n_cache = cp.cs;
-    const int us = cp.cs + cp.ts, s0 = cp.s;
-    const int n_st = us - s0 < n_my - it ? us - s0 : n_my - it;
-    const bool whole = s0 == 0 && n_st == us;
-    const int unit = cp.b * p.H + cp.h;
-#ifdef PROPD_TIMING_NO_MATH  // timing experiment: stream only
-    const bool active = false;
-#else
-    const bool active = wave * 32 < T;  // wave-uniform: some query of this wave exists
+  // ---- a piece: the part of one unit that lies in this range
+  struct Piece {
+    int L, T, n_cache, s0, n_st, unit, b, n_cmp;
+    bool whole;
+  };
+  auto piece_at = [&](const Cursor &c, int n_done) {
+    Piece pc;
+    pc.L = c.L;
+    pc.T = c.T;
+    pc.n_cache = c.cs;
+    pc.s0 = c.s;
+    const int us = c.cs + c.ts;
+    pc.n_st = us - c.s < n_my - n_done ? us - c.s : n_my - n_done;
+    pc.whole = c.s == 0 && pc.n_st == us;
+    pc.unit = c.b * p.H + c.h;
+    pc.b = c.b;
+    // Stages this wave has math for: none if its 32 query columns lie beyond the tree; tree
+    // rows after its last query are descendants or strangers of all its queries, and those
+    // stages are the last of the unit.
+    pc.n_cmp = 0;
+#ifndef PROPD_TIMING_NO_MATH  // timing experiment: stream only
+    if (wave * 32 < c.T) {
+      pc.n_cmp = c.cs + wave + 1 - c.s;
+      pc.n_cmp = pc.n_cmp > pc.n_st ? pc.n_st : (pc.n_cmp < 0 ? 0 : pc.n_cmp);
+    }
 #endif
+    return pc;
+  };
 
-    // Q^T fragments: B operand, lane = query column, 8 consecutive d per K step
-    bf16x8 qf[8];
-    uint64_t anc_lo = 0, anc_hi = 0;
-    {
-      const u32x4 zero4 = {0u, 0u, 0u, 0u};
-      const uint16_t *qrow = p.q + ((size_t)unit * p.T_max + (t < T ? t : 0)) * kD + g * 8;
+  // Q^T fragments (B operand: lane = query column, 8 consecutive d per K step) and the
+  // ancestor set of this lane's node.  Lanes past the tree take node 0: valid memory, and
+  // their columns are never stored.
+  u32x4 qf[8], ancv;
+  auto load_queries = [&](const Piece &pc) {
+    const int tq = t < pc.T ? t : 0;
+    const uint16_t *qrow = p.q + ((size_t)pc.unit * p.T_max + tq) * kD + g * 8;
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        u32x4 v = t < T ? *reinterpret_cast<const u32x4 *>(qrow + ks * 16) : zero4;
-        qf[ks] = __builtin_bit_cast(bf16x8, v);
-      }
-      if (t < T) {
-        anc_lo = p.anc[((size_t)cp.b * p.T_max + t) * 2];
-        anc_hi = p.anc[((size_t)cp.b * p.T_max + t) * 2 + 1];
-      }
-      // Touch the loaded registers here, so that the wait for them is placed before the
-      // stage loop and not inside it, where it would also drain the ring's loads in flight.
+    for (int ks = 0; ks < 8; ++ks) qf[ks] = global_load16_untracked(qrow + ks * 16);
+    ancv = global_load16_untracked(p.anc + ((size_t)pc.b * p.T_max + tq) * 2);
+#ifdef PROPD_COUNT_QUERY_LOADS
+    vm_a += 9;
+#endif
+    q_after = 0;
+  };
+  auto wait_queries = [&]() {
+    // the registers are named so that their uses cannot be scheduled above the wait
+    auto tie = [&]() {
+      asm volatile("" : "+v"(qf[0]), "+v"(qf[1]), "+v"(qf[2]), "+v"(qf[3]), "+v"(qf[4]), "+v"(qf[5]),
+                        "+v"(qf[6]), "+v"(qf[7]), "+v"(ancv));
+    };
+    tie();
+#ifdef PROPD_COUNT_QUERY_LOADS
+    wait_vmem_upto(q_after);
+#else
+    wait_vmem<0>();
+#endif
+    tie();
+  };
+
+  float m_run, l_run;
+  f32x16 o_acc[4];
+  u32x2 vt[2][8];
+  // S^T = K . Q^T of one stage
+  auto scores = [&](int sl) -> f32x16 {
+    const uint32_t so = (uint32_t)sl * kStageBytes;
+    f32x16 acc;
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) asm volatile("" ::"v"(qf[ks]));
-      asm volatile("" ::"v"(anc_lo), "v"(anc_hi));
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      const bf16x8 a = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8 *>(
+          (uintptr_t)(k_rd[ks] + so));
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, qf[ks]), acc, 0, 0, 0);
     }
+    return acc;
+  };
+  // start the transposing reads of a whole V stage: vt[ks2][2*mb + hi]
+  auto read_v = [&](int sl) {
+    const uint32_t so = (uint32_t)sl * kStageBytes;
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb) {
+      vt[0][2 * mb] = lds_read_tr16<0>(v_rd[mb][0] + so);
+      vt[0][2 * mb + 1] = lds_read_tr16<0>(v_rd[mb][1] + so);
+    }
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb) {
+      vt[1][2 * mb] = lds_read_tr16<16 * kRowBytes>(v_rd[mb][0] + so);
+      vt[1][2 * mb + 1] = lds_read_tr16<16 * kRowBytes>(v_rd[mb][1] + so);
+    }
+  };
+  // O^T += V^T . P^T with the V registers read last and the given weights
+  auto weighted_sum = [&](const uint32_t (&pw)[8]) {
+    wait_lds<0>(vt[0]);
+    wait_lds<0>(vt[1]);
+#pragma unroll
+    for (int ks2 = 0; ks2 < 2; ++ks2) {
+      const u32x4 pv = {pw[4 * ks2], pw[4 * ks2 + 1], pw[4 * ks2 + 2], pw[4 * ks2 + 3]};
+      const bf16x8 pf = __builtin_bit_cast(bf16x8, pv);
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb) {
+        const u32x4 aw = {vt[ks2][2 * mb].x, vt[ks2][2 * mb].y, vt[ks2][2 * mb + 1].x,
+                          vt[ks2][2 * mb + 1].y};
+        o_acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, aw), pf,
+                                                            o_acc[mb], 0, 0, 0);
+      }
+    }
+  };
 
-    float m_run = -INFINITY, l_run = 0.f;
-    f32x16 o_acc[4];
+  const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3f803f80u);
+  // a new running maximum is adopted only when it exceeds the reference by 2^8 in the
+  // exponent; below that the weights simply exceed 1, by a factor fp32 sums and bf16 hold
+  const float tau = 8.f / p.scale_log2e;
+
+  Piece pc = piece_at(cp, 0);
+  if (pc.n_cmp > 0) load_queries(pc);
+  while (n_acq < n_my) {
+    const int L = pc.L, T = pc.T, n_cache = pc.n_cache, s0 = pc.s0;
+    m_run = -INFINITY;
+    l_run = 0.f;
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) o_acc[mb][r] = 0.f;
 
-    for (int i = 0; i < n_st; ++i, ++it) {
-      // stage `it` has landed once at most the loads of the NS-2 stages issued after it
-      // (4 per wave and stage) are outstanding; near the end of the range fewer follow it
-      if (it + NS - 2 <= n_my - 1) wait_vmem<4 * (NS - 2)>(); else wait_vmem<0>();
-      __builtin_amdgcn_s_barrier();  // stage `it` is visible; every wave is done with stage it-1
-#ifdef PROPD_TIMING_NO_LOADS  // timing experiment: math on whatever the ring holds
-      if (false) {
-#else
-      if (it + NS - 1 < n_my) {
-#endif
-        issue(slot_ld);  // refill the slot of stage it-1
-        slot_ld = slot_ld + 1 == NS ? 0 : slot_ld + 1;
-      }
-      const unsigned char *st = smem + slot * kStageBytes;
-      slot = slot + 1 == NS ? 0 : slot + 1;
-
-      const int s = s0 + i;
-      const bool is_tree = s >= n_cache;
-      const int j0 = (is_tree ? s - n_cache : s) * kStageRows;
-      // tree rows after this wave's last query are descendants or strangers of all its queries
-      if (!active || (is_tree && j0 > wave * 32 + 31)) continue;
-      int n_valid = (is_tree ? T : L) - j0;
-      n_valid = n_valid > kStageRows ? kStageRows : n_valid;
-      const bool partial = is_tree || n_valid < kStageRows;  // uniform over the workgroup
-
-      // ---- S^T = K . Q^T
-      f32x16 sc;
+    if (pc.n_cmp > 0) {
+      // The loop is software-pipelined over stages so that matrix and vector work of
+      // different stages sit in one basic block: iteration i computes the scores of stage
+      // i+1 (MFMA), the softmax weights of stage i (VALU), and adds stage i-1 to O (MFMA).
+      int sl_cur = acquire();
+      wait_queries();
+      const uint64_t anc_lo = ((uint64_t)ancv.y << 32) | ancv.x, anc_hi = ((uint64_t)ancv.w << 32) | ancv.z;
+      f32x16 sc = scores(sl_cur);
+      uint32_t pw_prev[8];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) sc[r] = 0.f;
+      for (int r = 0; r < 8; ++r) pw_prev[r] = 0u;
+
+      auto stage = [&](int i, auto has_next, auto has_prev) {
+        constexpr bool kNext = decltype(has_next)::value, kPrev = decltype(has_prev)::value;
+        int sl_next = 0;
+        if (kNext) sl_next = acquire();
+        mfma_settle();  // sc was written by MFMAs of the previous iteration or the prologue
+
+        const int s = s0 + i;
+        const bool is_tree = s >= n_cache;
+        const int j0 = (is_tree ? s - n_cache : s) * kStageRows;
+        int n_valid = (is_tree ? T : L) - j0;
+        n_valid = n_valid > kStageRows ? kStageRows : n_valid;
+        // ---- mask (the softmax scale is positive, so it commutes with max and is applied
+        //      inside the exponent).  Register r of a 32x32 accumulator holds row
+        //      8*(r/4) + 4*g + r%4 of the block, i.e. K/V row j0 + that.
+        if (is_tree || n_valid < kStageRows) {  // uniform over the workgroup
+          // visibility of the stage's rows to this lane's query: cached rows below L for
+          // every query, tree rows only where the node's ancestor set has the bit
+          uint32_t vis = n_valid >= 32 ? ~0u : ((1u << n_valid) - 1u);
+          const uint64_t word = j0 >= 64 ? anc_hi : anc_lo;  // tree stages start at 0, 32, 64, 96
+          vis &= is_tree ? (uint32_t)(word >> (j0 & 32)) : ~0u;
+          vis >>= 4 * g;
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(st + k_rd[ks]);
-        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], sc, 0, 0, 0);
+          for (int r = 0; r < 16; ++r)
+            sc[r] = ((vis >> (8 * (r >> 2) + (r & 3))) & 1u) ? sc[r] : -INFINITY;
+        }
+        // ---- running maximum
+        float m_blk = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) m_blk = fmaxf(m_blk, sc[r]);
+        m_blk = fmaxf(m_blk, __shfl_xor(m_blk, 32, kWave));
+        if (__builtin_amdgcn_ballot_w64(m_blk > m_run + tau) != 0) {
+          // rare: move the reference.  O must first receive the stage still pending, whose
+          // weights are relative to the old reference.
+          if (kPrev) {
+            weighted_sum(pw_prev);
+#pragma unroll
+            for (int r = 0; r < 8; ++r) pw_prev[r] = 0u;
+            mfma_settle();
+          }
+          const float m_new = fmaxf(m_run, m_blk);
+          const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+          const float alpha = fast_exp2((m_run - m_safe) * p.scale_log2e);
+          l_run *= alpha;
+#pragma unroll
+          for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o_acc[mb][r] *= alpha;
+          m_run = m_new;
+        }
+        const float neg_m = -(m_run == -INFINITY ? 0.f : m_run) * p.scale_log2e;
+
+        // ---- one block: scores of the next stage, weights of this one, O update of the last
+        f32x16 sc_next;
+        if (kNext) sc_next = scores(sl_next);
+        uint32_t pw[8];
+#pragma unroll
+        for (int r = 0; r < 16; r += 2) {
+          const float p0 = fast_exp2(fmaf(sc[r], p.scale_log2e, neg_m));
+          const float p1 = fast_exp2(fmaf(sc[r + 1], p.scale_log2e, neg_m));
+          pw[r >> 1] = cvt_pk_bf16(p0, p1);
+          // the row sums are taken over the rounded bf16 weights, the values the MFMA multiplies
+          l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pw[r >> 1]), ones,
+                                                  l_run, false);
+        }
+        if (kPrev) weighted_sum(pw_prev);
+        read_v(sl_cur);  // V of this stage, used by the next iteration or the drain
+#pragma unroll
+        for (int r = 0; r < 8; ++r) pw_prev[r] = pw[r];
+        if (kNext) {
+          sc = sc_next;
+          sl_cur = sl_next;
+        }
+      };
+      using yes = std::true_type;
+      using no = std::false_type;
+      if (pc.n_cmp == 1) {
+        stage(0, no{}, no{});
+      } else {
+        stage(0, yes{}, no{});
+        for (int i = 1; i < pc.n_cmp - 1; ++i) stage(i, yes{}, yes{});
+        stage(pc.n_cmp - 1, no{}, yes{});
       }
+      weighted_sum(pw_prev);  // drain
       mfma_settle();
+    }
+    // stages of the piece without math for this wave: keep the ring and the barriers going
+    for (int i = pc.n_cmp; i < pc.n_st; ++i) acquire();
 
-      // ---- start the transposing reads of the whole V stage now; they complete while the
-      //      softmax below runs.  vt[ks2][2*mb + hi]: k-step ks2 (16 rows), d block mb.
-      u32x2 vt[2][8];
-      {
-        const uint32_t vs = smem_base + (uint32_t)(st - smem);
-#pragma unroll
-        for (int mb = 0; mb < 4; ++mb) {
-          vt[0][2 * mb] = lds_read_tr16<0>(vs + v_rd[mb][0]);
-          vt[0][2 * mb + 1] = lds_read_tr16<0>(vs + v_rd[mb][1]);
-        }
-#pragma unroll
-        for (int mb = 0; mb < 4; ++mb) {
-          vt[1][2 * mb] = lds_read_tr16<16 * kRowBytes>(vs + v_rd[mb][0]);
-          vt[1][2 * mb + 1] = lds_read_tr16<16 * kRowBytes>(vs + v_rd[mb][1]);
-        }
-      }
-
-      // ---- mask and running max on the raw scores (the softmax scale is positive, so it
-      //      commutes with max and is applied inside the exponent).  Register r of a 32x32
-      //      accumulator holds row 8*(r/4) + 4*g + r%4 of the block, i.e. K/V row j0 + that.
-      if (partial) {
-        // visibility of the stage's rows to this lane's query: cached rows below L for every
-        // query, tree rows only where the node's ancestor set has the bit
-        uint32_t vis = n_valid >= 32 ? ~0u : ((1u << n_valid) - 1u);
-        const uint64_t word = j0 >= 64 ? anc_hi : anc_lo;  // tree stages start at 0, 32, 64, 96
-        vis &= is_tree ? (uint32_t)(word >> (j0 & 32)) : ~0u;
-        vis >>= 4 * g;
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-          sc[r] = ((vis >> (8 * (r >> 2) + (r & 3))) & 1u) ? sc[r] : -INFINITY;
-      }
-      float m_blk = -INFINITY;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) m_blk = fmaxf(m_blk, sc[r]);
-      m_blk = fmaxf(m_blk, __shfl_xor(m_blk, 32, kWave));
-      const float m_new = fmaxf(m_run, m_blk);
-      const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-      // rescale only when some query of this wave saw a new maximum
-      if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
-        const float alpha = fast_exp2((m_run - m_safe) * p.scale_log2e);
-        l_run *= alpha;
-#pragma unroll
-        for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) o_acc[mb][r] *= alpha;
-        m_run = m_new;
-      }
-      const float neg_m = -m_safe * p.scale_log2e;
-
-      // ---- P^T (bf16) straight from the score registers, then O^T += V^T . P^T.  The row
-      //      sums are taken over the rounded bf16 weights, the same values the MFMA multiplies.
-      const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3f803f80u);
-      uint32_t pw[8];
-#pragma unroll
-      for (int r = 0; r < 16; r += 2) {
-        const float p0 = fast_exp2(fmaf(sc[r], p.scale_log2e, neg_m));
-        const float p1 = fast_exp2(fmaf(sc[r + 1], p.scale_log2e, neg_m));
-        pw[r >> 1] = cvt_pk_bf16(p0, p1);
-        l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pw[r >> 1]), ones, l_run,
-                                                false);
-      }
-      wait_lds<8>(vt[0]);  // LDS reads return in order: the first eight are in
-#pragma unroll
-      for (int ks2 = 0; ks2 < 2; ++ks2) {
-        if (ks2 == 1) wait_lds<0>(vt[1]);
-        const u32x4 pv = {pw[4 * ks2], pw[4 * ks2 + 1], pw[4 * ks2 + 2], pw[4 * ks2 + 3]};
-        const bf16x8 pf = __builtin_bit_cast(bf16x8, pv);
-#pragma unroll
-        for (int mb = 0; mb < 4; ++mb) {
-          const u32x4 aw = {vt[ks2][2 * mb].x, vt[ks2][2 * mb].y, vt[ks2][2 * mb + 1].x,
-                            vt[ks2][2 * mb + 1].y};
-          o_acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, aw), pf,
-                                                              o_acc[mb], 0, 0, 0);
-        }
-      }
+    // ---- the next piece's queries are requested before this piece's results are stored:
+    //      waiting for them later then does not wait for the stores
+    const Piece done = pc;
+    cp.advance(map, done.n_st);
+    if (n_acq < n_my) {
+      pc = piece_at(cp, n_acq);
+      if (pc.n_cmp > 0) load_queries(pc);
     }
 
     // ---- write: lane holds d = mb*32 + 8*(r/4) + 4*g + r%4 for its query t
-    mfma_settle();
     l_run += __shfl_xor(l_run, 32, kWave);
     m_run *= p.scale_log2e;  // from here on the maximum is in the exponent's (log2) domain
-    if (t < T) {
-      if (whole) {
-        const float inv = 1.f / l_run;
-        uint16_t *orow = p.out + ((size_t)unit * p.T_max + t) * kD;
-#pragma unroll
-        for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-          for (int q4 = 0; q4 < 4; ++q4) {
-            u32x2 w2;
-            w2.x = cvt_pk_bf16(o_acc[mb][4 * q4] * inv, o_acc[mb][4 * q4 + 1] * inv);
-            w2.y = cvt_pk_bf16(o_acc[mb][4 * q4 + 2] * inv, o_acc[mb][4 * q4 + 3] * inv);
-            *reinterpret_cast<u32x2 *>(orow + mb * 32 + 8 * q4 + 4 * g) = w2;
-          }
+#ifdef PROPD_TIMING_NO_WRITE  // timing experiment: no output
+    if (wave * 32 < T && l_run == 12345.f) {
+#else
+    if (wave * 32 < T) {  // wave-uniform: the stores below are issued, and counted
+#endif
+      int n_stores;
+      if (done.whole) {
+        if (t < T)
+          store_out_row<true>(p.out + ((size_t)done.unit * p.T_max + t) * kD, o_acc, 1.f / l_run, g);
+        n_stores = kOutRowStores;
       } else {
         // a range starts inside at most one unit and ends inside at most one
         const size_t ps = 2 * (size_t)w + (s0 > 0 ? 0 : 1);
-        float *po = p.part_o + (ps * 128 + t) * kD;
+        if (t < T) {
 #pragma unroll
-        for (int mb = 0; mb < 4; ++mb)
+          for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-          for (int q4 = 0; q4 < 4; ++q4) {
-            const f32x4 w4 = {o_acc[mb][4 * q4], o_acc[mb][4 * q4 + 1], o_acc[mb][4 * q4 + 2],
-                              o_acc[mb][4 * q4 + 3]};
-            *reinterpret_cast<f32x4 *>(po + mb * 32 + 8 * q4 + 4 * g) = w4;
-          }
-        if (g == 0) {
-          p.part_ml[(ps * 128 + t) * 2] = m_run;
-          p.part_ml[(ps * 128 + t) * 2 + 1] = l_run;
+            for (int q4 = 0; q4 < 4; ++q4) {
+              const f32x4 w4 = {o_acc[mb][4 * q4], o_acc[mb][4 * q4 + 1], o_acc[mb][4 * q4 + 2],
+                                o_acc[mb][4 * q4 + 3]};
+              global_store16_untracked(p.part_o + part_o_index(ps, wave, 4 * mb + q4, lane),
+                                       __builtin_bit_cast(u32x4, w4));
+            }
+          global_store4_untracked(p.part_ml + part_ml_index(ps, wave, 0, lane), m_run);
+          global_store4_untracked(p.part_ml + part_ml_index(ps, wave, 1, lane), l_run);
         }
+        n_stores = 18;
       }
+#ifdef PROPD_COUNT_STORES
+      vm_a += n_stores;
+      q_after += n_stores;
+#else
+      (void)n_stores;
+#endif
     }
-    cp.advance(map, n_st);
   }
 }
 
 // Finish the units that a range boundary cut: out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s
-// over the workgroups s that hold a piece.  One workgroup per unit; whole units return at once.
+// over the workgroups s that hold a piece.  One workgroup per unit, threads mapped to
+// (query, d) exactly as in the main kernel; whole units return at once.
 __global__ __launch_bounds__(kAttnThreads) void tree_attn_combine_kernel(AttnParams p, int G) {
   const int unit = blockIdx.x;
   const int b = unit / p.H, h = unit - b * p.H;
@@ -456,9 +677,9 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_combine_kernel(AttnPar
     if (bb == b) b_start = n_total;
     n_total += (long long)p.H * map.unit_stages(bb);
   }
-  const int ut = map.unit_stages(b), T = map.nodes(b);
-  const long long S = b_start + (long long)h * ut, E = S + ut;
-  // workgroup that owns tile x: the largest w with range_start(w) <= x
+  const int us = map.unit_stages(b), T = map.nodes(b);
+  const long long S = b_start + (long long)h * us, E = S + us;
+  // workgroup that owns stage x: the largest w with range_start(w) <= x
   auto owner = [&](long long x) {
     long long w = x * G / n_total;
     while (w + 1 < G && range_start(w + 1, n_total, G) <= x) ++w;
@@ -467,37 +688,40 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_combine_kernel(AttnPar
   };
   const long long w_first = owner(S), w_last = owner(E - 1);
   if (w_first == w_last) return;  // the unit was finished by one workgroup
-  // partial slots of the pieces, worked out once per workgroup
-  __shared__ int s_slot[kMaxGrid];
-  const int pieces = (int)(w_last - w_first + 1);
-  for (int i = threadIdx.x; i < pieces; i += kAttnThreads) {
-    const long long w = w_first + i;
-    s_slot[i] = (int)(2 * w + (range_start(w, n_total, G) > S ? 0 : 1));
-  }
-  __syncthreads();
-  for (int item = threadIdx.x; item < T * (kD / 4); item += kAttnThreads) {
-    const int t = item / (kD / 4), d4 = (item - t * (kD / 4)) * 4;
-    float M = -INFINITY;
-    for (int i = 0; i < pieces; ++i)
-      M = fmaxf(M, p.part_ml[((size_t)s_slot[i] * 128 + t) * 2]);
-    if (M == -INFINITY) M = 0.f;
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    float lsum = 0.f;
-    for (int i = 0; i < pieces; ++i) {
-      const size_t slot = (size_t)s_slot[i];
-      const float wgt = fast_exp2(p.part_ml[(slot * 128 + t) * 2] - M);
-      lsum += wgt * p.part_ml[(slot * 128 + t) * 2 + 1];
-      if (wgt != 0.f) {
-        const f32x4 o = *reinterpret_cast<const f32x4 *>(p.part_o + (slot * 128 + t) * kD + d4);
-        acc += o * wgt;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int t = wave * 32 + (lane & 31), g = lane >> 5;
+  if (wave * 32 >= T) return;
+  f32x16 acc[4];
+#pragma unroll
+  for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[mb][r] = 0.f;
+  float M = -INFINITY, lsum = 0.f;
+  for (long long wg = w_first; wg <= w_last; ++wg) {
+    const size_t ps = 2 * (size_t)wg + (range_start(wg, n_total, G) > S ? 0 : 1);
+    const float m = p.part_ml[part_ml_index(ps, wave, 0, lane)];
+    const float l = p.part_ml[part_ml_index(ps, wave, 1, lane)];
+    const float M_new = fmaxf(M, m);
+    const float M_safe = M_new == -INFINITY ? 0.f : M_new;
+    const float a_old = fast_exp2(M - M_safe), a_new = fast_exp2(m - M_safe);
+    lsum = lsum * a_old + l * a_new;
+    M = M_new;
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const f32x4 o = *reinterpret_cast<const f32x4 *>(p.part_o + part_o_index(ps, wave, 4 * mb + q4, lane));
+        acc[mb][4 * q4] = acc[mb][4 * q4] * a_old + o.x * a_new;
+        acc[mb][4 * q4 + 1] = acc[mb][4 * q4 + 1] * a_old + o.y * a_new;
+        acc[mb][4 * q4 + 2] = acc[mb][4 * q4 + 2] * a_old + o.z * a_new;
+        acc[mb][4 * q4 + 3] = acc[mb][4 * q4 + 3] * a_old + o.w * a_new;
       }
-    }
-    const float inv = 1.f / lsum;
-    u32x2 w2;
-    w2.x = cvt_pk_bf16(acc.x * inv, acc.y * inv);
-    w2.y = cvt_pk_bf16(acc.z * inv, acc.w * inv);
-    *reinterpret_cast<u32x2 *>(p.out + ((size_t)unit * p.T_max + t) * kD + d4) = w2;
   }
+  // lanes beyond the tree read unwritten scratch and store nothing; the two lanes of an
+  // exchange pair hold the same query, so they are active together
+  if (t < T)
+    store_out_row<false>(p.out + ((size_t)unit * p.T_max + t) * kD, acc, 1.f / lsum, g);
 }
 
 // ------------------------------------------------------------------------------------
