@@ -60,6 +60,11 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", type=int, default=4, choices=[2, 3, 4, 5])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0,
+                    help="CPU work the oracle baseline is bounded to (whole sequences)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a plain 1 GiB device copy (the reference kernel that the "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; nothing here uses a second one "
@@ -77,6 +82,8 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        return copy_calibration(torch)
     w = synth.WORKLOADS[args.workload]
     att, pr, acc, token = build_inputs(w, synth)
     B, H, d, T_max, L_max = att["B"], att["H"], att["d"], att["T_max"], att["L_max"]
@@ -179,9 +186,11 @@ def main() -> int:
                    "mean_accept_len": float(accept_len.mean())},
         "parts_us": {"attention_full_tree": att_full_ms * 1e3, "early_prune": prune_ms * 1e3,
                      "attention_compacted_tree": att_small_ms * 1e3, "accept": accept_ms * 1e3},
-        "roofline": {"kernel": "tree_attn_bf16_kernel (full tree) + combine", "bound": "hbm",
+        "roofline": {"kernel": "propd_tree_attention on the full tree: tree_attn_bf16_kernel "
+                               "+ tree_attn_combine_kernel", "bound": "hbm",
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": recorded_traffic(w.name),
                      "algorithmic_bytes": alg_bytes,
                      "kv_stream_gbps": kv_bytes / (att_full_ms * 1e-3) / 1e9,
                      "kv_stream_frac": kv_bytes / (att_full_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
@@ -190,53 +199,88 @@ def main() -> int:
     }
 
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, att, pr, acc, token)
+        result["cpu_baseline"] = cpu_baseline(w, att, pr, acc, token, args.cpu_seconds)
     print(json.dumps(result), flush=True)
     return 0
 
 
-def cpu_baseline(w, att, pr, acc, token):
-    """The oracle, as it stands, timed on this host on a bounded sample of the workload:
-    the first `Bs` sequences through the same four parts.  A reported baseline only."""
+def recorded_traffic(workload_name):
+    """HBM bytes per full-tree attention launch, from the rocprofv3 counter runs summarised
+    under profiles/ (FETCH_SIZE + WRITE_SIZE, scaled by the copy-kernel calibration); None if
+    no such summary exists for this workload."""
+    path = os.path.join(ROOT, "profiles", f"{workload_name}_tree_attention_hbm_traffic.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch"):
+                    return float(line.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
+def copy_calibration(torch):
+    """A plain device-to-device copy of 1 GiB (reads 1 GiB, writes 1 GiB), three times."""
+    n = 1 << 30
+    src = torch.full((n,), 7, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    print(json.dumps({"copy_bytes_read": n, "copy_bytes_written": n, "launches": 3}), flush=True)
+    return 0
+
+
+def cpu_baseline(w, att, pr, acc, token, budget_s):
+    """The oracle, as it stands, timed on this host on a bounded sample of the workload: whole
+    sequences (all heads) through the same four parts, one sequence at a time, until about
+    `budget_s` seconds of CPU work are spent.  A reported baseline only."""
     from oracle import oracle
     oracle.build()
-    Bs = w.B
-    Hs = att["H"]
-    sl = slice(0, Bs)
-    hs = slice(0, Hs)
-    cut = lambda a: np.ascontiguousarray(a[sl][:, hs])
-    n_nodes, parent, seq = att["n_nodes"][sl], att["parent"][sl], att["seq_lens"][sl]
-    q, kc, vc, kt, vt = (cut(att[k]) for k in ("q", "k_cache", "v_cache", "k_tree", "v_tree"))
-    t0 = time.perf_counter()
-    oracle.tree_attention(n_nodes, parent, seq, q, kc, vc, kt, vt, att["scale"])
-    t_att = time.perf_counter() - t0
-    t_pr = t_att2 = 0.0
-    tree2 = (n_nodes, parent, token[sl])
-    logits = acc["logits"][sl]
-    if pr is not None:
+    secs = {"attention_full_tree": 0.0, "early_prune": 0.0, "attention_compacted_tree": 0.0,
+            "accept": 0.0}
+    done_tokens, done_seqs = 0, 0
+    t_begin = time.perf_counter()
+    for b in range(w.B):
+        sl = slice(b, b + 1)
+        cut = lambda a: np.ascontiguousarray(a[sl])
+        n_nodes, parent, seq = att["n_nodes"][sl], att["parent"][sl], att["seq_lens"][sl]
+        q, kc, vc, kt, vt = (cut(att[k]) for k in ("q", "k_cache", "v_cache", "k_tree", "v_tree"))
         t0 = time.perf_counter()
-        rank, _ = oracle.early_head_rank(n_nodes, parent, token[sl], pr["hidden_states"][sl],
-                                         pr["head_weight"], w.top_k)
-        c = oracle.prune_compact(n_nodes, parent, token[sl], rank, w.top_k)
-        g = lambda a: oracle.gather_rows(a, c["orig_index"], c["n_kept"])
-        q2, kt2, vt2 = g(q), g(kt), g(vt)
-        g(pr["hidden_states"][sl])
-        t_pr = time.perf_counter() - t0
-        logits = g(logits)
+        oracle.tree_attention(n_nodes, parent, seq, q, kc, vc, kt, vt, att["scale"])
+        secs["attention_full_tree"] += time.perf_counter() - t0
+        tree2 = (n_nodes, parent, token[sl])
+        logits = acc["logits"][sl]
+        if pr is not None:
+            t0 = time.perf_counter()
+            rank, _ = oracle.early_head_rank(n_nodes, parent, token[sl], pr["hidden_states"][sl],
+                                             pr["head_weight"], w.top_k)
+            c = oracle.prune_compact(n_nodes, parent, token[sl], rank, w.top_k)
+            g = lambda a: oracle.gather_rows(a, c["orig_index"], c["n_kept"])
+            q2, kt2, vt2 = g(q), g(kt), g(vt)
+            g(pr["hidden_states"][sl])
+            secs["early_prune"] += time.perf_counter() - t0
+            logits = g(logits)
+            t0 = time.perf_counter()
+            oracle.tree_attention(c["n_kept"], c["parent"], seq, q2, kc, vc, kt2, vt2, att["scale"])
+            secs["attention_compacted_tree"] += time.perf_counter() - t0
+            tree2 = (c["n_kept"], c["parent"], c["token"])
         t0 = time.perf_counter()
-        oracle.tree_attention(c["n_kept"], c["parent"], seq, q2, kc, vc, kt2, vt2, att["scale"])
-        t_att2 = time.perf_counter() - t0
-        tree2 = (c["n_kept"], c["parent"], c["token"])
-    t0 = time.perf_counter()
-    oracle.accept_path(tree2[0], tree2[1], tree2[2], logits)
-    t_acc = time.perf_counter() - t0
-    total = t_att + t_att2 + t_pr + t_acc
-    return {"value": float(n_nodes.sum()) / total, "unit": "tokens/s", "cores": oracle.threads(),
+        oracle.accept_path(tree2[0], tree2[1], tree2[2], logits)
+        secs["accept"] += time.perf_counter() - t0
+        done_tokens += int(n_nodes.sum())
+        done_seqs += 1
+        spent = time.perf_counter() - t_begin
+        log(f"cpu baseline: sequence {b} done, {spent:.1f}s")
+        if spent >= budget_s or spent * (done_seqs + 1) / done_seqs > 2.0 * budget_s:
+            break
+    total = sum(secs.values())
+    secs["total"] = total
+    return {"value": done_tokens / total, "unit": "tokens/s", "cores": oracle.threads(),
             "kind": "oracle",
-            "sample": f"{Bs} of {w.B} sequences, all heads, through the same four parts "
-                      f"({int(n_nodes.sum())} tree tokens)",
-            "seconds": {"attention_full_tree": t_att, "early_prune": t_pr,
-                        "attention_compacted_tree": t_att2, "accept": t_acc, "total": total}}
+            "sample": f"the first {done_seqs} of {w.B} sequences, all heads, through the same "
+                      f"four parts ({done_tokens} tree tokens, {total:.1f} s)",
+            "seconds": secs}
 
 
 if __name__ == "__main__":

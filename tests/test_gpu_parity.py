@@ -136,6 +136,32 @@ def test_attention_bf16_many_splits(pb, oracle):
     check_attention(oracle, x, out, sent)
 
 
+@pytest.mark.parametrize("direction", ["rising", "falling", "late_spike"])
+def test_attention_bf16_moving_maximum(pb, oracle, direction):
+    """Scores whose running maximum keeps moving by many powers of two (keys scaled along the
+    cache), so the kernel's reference-maximum updates, with an earlier stage's weights still
+    to be added, are exercised in every position; and scores that only ever shrink, where the
+    first reference must last."""
+    rng = np.random.default_rng(31)
+    shapes = [synth.rank_product_tree(128, 5), synth.random_tree(rng, 50)]
+    x = small_bf16_case(31, 2, 2, 128, shapes, [700, 333], L_max=704)
+    k = synth.as_float(x["k_cache"]).astype(np.float32)
+    q = synth.as_float(x["q"]).astype(np.float32)
+    L = k.shape[2]
+    pos = np.arange(L, dtype=np.float32)
+    if direction == "rising":
+        gain = 0.2 + 6.0 * pos / L
+    elif direction == "falling":
+        gain = 6.0 - 5.8 * pos / L
+    else:
+        gain = np.where((pos > 500) & (pos < 520), 8.0, 0.3).astype(np.float32)
+    # keys aligned with query 0 of each head so that the gain really moves the scores
+    k = 0.3 * k + gain[None, None, :, None] * q[:, :, :1, :] / 4.0
+    x["k_cache"] = synth.f32_to_bf16_bits(k.astype(np.float32))
+    out, sent = run_attention(pb, x)
+    check_attention(oracle, x, out, sent)
+
+
 def test_attention_survivors_unchanged_by_compaction(pb, oracle):
     """Section 4.1: pruning does not change what a surviving node computes."""
     rng = np.random.default_rng(12)
