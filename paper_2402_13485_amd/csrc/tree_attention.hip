@@ -172,21 +172,37 @@ __device__ __forceinline__ size_t part_ml_index(size_t slot, int wave, int which
 }
 
 // Work decomposition shared by the main kernel and the merge kernel.  The work of one
-// call is the list of K/V stages of all (sequence, head) units in order, each unit's
-// cached stages followed by its tree stages.  Workgroup w of G owns the contiguous range
-// [w*N/G, (w+1)*N/G) of that list, so every workgroup streams the same number of rows
-// whatever the mix of sequence lengths; a unit cut by a range boundary is finished by
-// the merge kernel from per-workgroup partial results.
+// call is made of K/V stages; a (sequence, head) unit is its cached stages followed by its
+// tree stages.  Workgroup w of G does, in this order,
+//   - k whole units w, w+G, ..., when all sequences have the same lengths (k = units / G):
+//     no partial results, and all workgroups write their outputs at the same moments, which
+//     the memory system takes far better than a trickle of stores into the read stream;
+//   - the contiguous range [w*N/G, (w+1)*N/G) of the list of the N stages of the remaining
+//     units (all units when lengths differ, so that every workgroup streams the same number
+//     of rows whatever the mix); a unit cut by a range boundary is finished by the merge
+//     kernel from per-workgroup partial results.
+// A wave-uniform 32-bit load through the scalar cache.  Issued as assembly: the compiler
+// would use a vector load here and wait for it with vmcnt(0), which drains the ring.
+__device__ __forceinline__ int32_t uniform_load_i32(const int32_t *ptr) {
+  const uint64_t a = (uint64_t)(uintptr_t)ptr;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
+  const uint64_t sa = ((uint64_t)hi << 32) | lo;  // in scalar registers
+  int32_t v;
+  asm volatile("s_load_dword %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(sa) : "memory");
+  return v;
+}
+
 struct StageMap {
   int B, H;
   const int32_t *seq_lens, *n_nodes;
   int L_max, T_max;
   __device__ __forceinline__ int len(int b) const {
-    const int L = seq_lens[b];
+    const int L = uniform_load_i32(seq_lens + b);
     return L < 0 ? 0 : (L > L_max ? L_max : L);
   }
   __device__ __forceinline__ int nodes(int b) const {
-    const int T = n_nodes[b];
+    const int T = uniform_load_i32(n_nodes + b);
     return T < 1 ? 1 : (T > T_max ? T_max : T);
   }
   __device__ __forceinline__ int cache_stages(int b) const {
@@ -196,10 +212,11 @@ struct StageMap {
     return (nodes(b) + kStageRows - 1) / kStageRows;
   }
   __device__ __forceinline__ int unit_stages(int b) const { return cache_stages(b) + tree_stages(b); }
-  __device__ long long total() const {
+  // stages of all units before unit (b, h) in the list of all units
+  __device__ long long stages_before(int b, int h) const {
     long long n = 0;
-    for (int b = 0; b < B; ++b) n += (long long)H * unit_stages(b);
-    return n;
+    for (int bb = 0; bb < b; ++bb) n += (long long)H * unit_stages(bb);
+    return n + (long long)h * unit_stages(b);
   }
 };
 
@@ -207,27 +224,105 @@ __device__ __forceinline__ long long range_start(long long w, long long n, long 
   return w * n / g;
 }
 
-// Position in the stage list: stage s of unit (b, h), with the sizes of sequence b.
-struct Cursor {
-  int b, h, s;
-  int L, T, cs, ts;  // cached rows, tree nodes, cached stages, tree stages of sequence b
+struct Schedule {
+  int k;                  // whole units per workgroup, done first
+  long long first_split;  // first unit of the split list (= k * G)
+  long long split_base;   // stages of the units before it
+  long long n_split;      // stages of the split list
+};
+
+__device__ __forceinline__ Schedule make_schedule(const StageMap &m, long long G) {
+  Schedule sc;
+  int us_min = 1 << 30, us_max = 0;
+  long long n_all = 0;
+  for (int b = 0; b < m.B; ++b) {
+    const int us = m.unit_stages(b);
+    us_min = us < us_min ? us : us_min;
+    us_max = us > us_max ? us : us_max;
+    n_all += (long long)m.H * us;
+  }
+  // whole units first only where they are (nearly) equally long: a workgroup's k of them
+  // then differ by at most a few percent between workgroups
+  const long long U = (long long)m.B * m.H;
+  sc.k = (us_max - us_min) * 32 <= us_max ? (int)(U / G) : 0;
+  sc.first_split = (long long)sc.k * G;
+  sc.split_base = sc.k > 0 ? m.stages_before((int)(sc.first_split / m.H), (int)(sc.first_split % m.H)) : 0;
+  sc.n_split = n_all - sc.split_base;
+  return sc;
+}
+
+// Position of a workgroup in its own sequence of stages: stage s of unit (b, h).
+struct Walk {
+  long long unit;  // b * H + h
+  int b, s;
+  int L, T, cs, ts;         // cached rows, tree nodes, cached stages, tree stages of sequence b
+  int whole_left;           // whole units still to do, this one included; 0 = in the split range
+  long long split_unit;     // where this workgroup's split range starts
+  int split_s;
   __device__ __forceinline__ void load_sizes(const StageMap &m) {
     L = m.len(b);
     T = m.nodes(b);
     cs = (L + kStageRows - 1) / kStageRows;
     ts = (T + kStageRows - 1) / kStageRows;
   }
-  __device__ __forceinline__ void advance(const StageMap &m, int n) {  // n <= stages left in the unit
-    s += n;
-    if (s == cs + ts) {
+  __device__ __forceinline__ void set_unit(const StageMap &m, long long u) {
+    unit = u;
+    const int nb = (int)(u / m.H);
+    if (nb != b) {
+      b = nb;
+      load_sizes(m);
+    }
+  }
+  // the workgroup's first stage; returns the number of stages it will do
+  __device__ int start(const StageMap &m, const Schedule &sc, long long w, long long G) {
+    const long long U = (long long)m.B * m.H;
+    const long long x0 = range_start(w, sc.n_split, G);
+    int n_my = (int)(range_start(w + 1, sc.n_split, G) - x0);
+    // locate stage split_base + x0 of the list of all units
+    const long long x = sc.split_base + x0;
+    b = 0;
+    long long b_start = 0;
+    while (b < m.B - 1 && x >= b_start + (long long)m.H * m.unit_stages(b)) {
+      b_start += (long long)m.H * m.unit_stages(b);
+      ++b;
+    }
+    load_sizes(m);
+    {
+      const int us = cs + ts;
+      const long long hh = (x - b_start) / us;
+      split_unit = (long long)b * m.H + hh;
+      split_s = (int)((x - b_start) - hh * us);
+    }
+    if (split_unit >= U) {  // an empty range at the very end: stay on valid memory
+      split_unit = U - 1;
+      split_s = 0;
+    }
+    whole_left = sc.k;
+    if (sc.k > 0) {
+      for (int j = 0; j < sc.k; ++j) n_my += m.unit_stages((int)((w + j * G) / m.H));
+      b = -1;
+      set_unit(m, w);
       s = 0;
-      if (++h == m.H) {
-        h = 0;
-        if (b + 1 < m.B) {
-          ++b;
-          load_sizes(m);
-        }
+    } else {
+      b = -1;
+      set_unit(m, split_unit);
+      s = split_s;
+    }
+    return n_my;
+  }
+  __device__ __forceinline__ void advance(const StageMap &m, long long G, int n) {
+    s += n;  // n <= stages left in the unit
+    if (s < cs + ts) return;
+    s = 0;
+    if (whole_left > 0) {
+      if (--whole_left > 0) {
+        set_unit(m, unit + G);
+      } else {
+        set_unit(m, split_unit);
+        s = split_s;
       }
+    } else if (unit + 1 < (long long)m.B * m.H) {
+      set_unit(m, unit + 1);
     }
   }
 };
@@ -245,26 +340,11 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnPar
   const int t = wave * 32 + l32;  // this lane's query column
 
   const StageMap map = {p.B, p.H, p.seq_lens, p.n_nodes, p.L_max, p.T_max};
-  const long long n_total = map.total();
   const long long G = gridDim.x, w = blockIdx.x;
-  const long long x0 = range_start(w, n_total, G);
-  const int n_my = (int)(range_start(w + 1, n_total, G) - x0);
+  const Schedule sch = make_schedule(map, G);
+  Walk cp;
+  const int n_my = cp.start(map, sch, w, G);
   if (n_my <= 0) return;
-
-  // ---- the first stage of this range
-  Cursor cp;
-  {
-    cp.b = 0;
-    long long b_start = 0;
-    while (cp.b < p.B - 1 && x0 >= b_start + (long long)p.H * map.unit_stages(cp.b)) {
-      b_start += (long long)p.H * map.unit_stages(cp.b);
-      ++cp.b;
-    }
-    cp.load_sizes(map);
-    const int us = cp.cs + cp.ts;
-    cp.h = (int)((x0 - b_start) / us);
-    cp.s = (int)((x0 - b_start) - (long long)cp.h * us);
-  }
 
   // ---- loader.  It walks the same stage list ahead of the math, one segment (the cached
   //      rows or the tree rows of a unit) at a time.  One direct load moves 64 lanes x 16
@@ -280,20 +360,18 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnPar
   const int ld_row = 4 * wave + (lane >> 4);
   const int k_lane_chunk = ((lane & 15) ^ ld_row) << 4;
   const int v_lane_chunk = ((lane & 15) ^ (((lane >> 4) << 2) | wave)) << 4;
-  int ld_b = cp.b, ld_h = cp.h, ld_L = cp.L, ld_T = cp.T;
-  bool ld_tree;
+  Walk lw = cp;  // the next stage to issue
   int ld_rows;                       // rows left in the segment, from the next stage to issue
   const unsigned char *ld_k, *ld_v;  // first row of the next stage to issue
-  auto ld_segment = [&](bool tree, int first_row) {
-    const size_t unit = (size_t)ld_b * p.H + ld_h;
-    ld_tree = tree;
-    ld_rows = (tree ? ld_T : ld_L) - first_row;
-    const size_t row0 = (tree ? unit * p.T_max : unit * p.L_max) + first_row;
+  auto ld_segment = [&]() {          // the segment (cached or tree rows) that stage lw.s starts
+    const bool tree = lw.s >= lw.cs;
+    const int first_row = (tree ? lw.s - lw.cs : lw.s) * kStageRows;
+    ld_rows = (tree ? lw.T : lw.L) - first_row;
+    const size_t row0 = (size_t)lw.unit * (tree ? p.T_max : p.L_max) + first_row;
     ld_k = reinterpret_cast<const unsigned char *>(tree ? p.k_tree : p.k_cache) + row0 * kRowBytes;
     ld_v = reinterpret_cast<const unsigned char *>(tree ? p.v_tree : p.v_cache) + row0 * kRowBytes;
   };
-  if (cp.s < cp.cs) ld_segment(false, cp.s * kStageRows);
-  else ld_segment(true, (cp.s - cp.cs) * kStageRows);
+  ld_segment();
   auto dma16 = [&](const unsigned char *src, unsigned char *dst) {
     __builtin_amdgcn_global_load_lds((global_void *)src, (lds_void *)dst, 16, 0, 2 /* nt */);
   };
@@ -315,23 +393,13 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnPar
         dma16(ld_v + (row * kRowBytes + v_lane_chunk), dst + kHalfStage + i * 16 * kRowBytes);
       }
     }
-    ld_rows -= kStageRows;
-    ld_k += kHalfStage;
-    ld_v += kHalfStage;
-    if (ld_rows <= 0) {
-      if (!ld_tree) {
-        ld_segment(true, 0);
-      } else {
-        if (++ld_h == p.H) {
-          ld_h = 0;
-          if (ld_b + 1 < p.B) {
-            ++ld_b;
-            ld_L = map.len(ld_b);
-            ld_T = map.nodes(ld_b);
-          }
-        }
-        ld_segment(ld_L == 0, 0);
-      }
+    lw.advance(map, G, 1);
+    if (ld_rows > kStageRows) {
+      ld_rows -= kStageRows;
+      ld_k += kHalfStage;
+      ld_v += kHalfStage;
+    } else {
+      ld_segment();  // the tree rows of the unit, or another unit
     }
   };
 
@@ -396,7 +464,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnPar
     int L, T, n_cache, s0, n_st, unit, b, n_cmp;
     bool whole;
   };
-  auto piece_at = [&](const Cursor &c, int n_done) {
+  auto piece_at = [&](const Walk &c, int n_done) {
     Piece pc;
     pc.L = c.L;
     pc.T = c.T;
@@ -405,7 +473,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnPar
     const int us = c.cs + c.ts;
     pc.n_st = us - c.s < n_my - n_done ? us - c.s : n_my - n_done;
     pc.whole = c.s == 0 && pc.n_st == us;
-    pc.unit = c.b * p.H + c.h;
+    pc.unit = (int)c.unit;
     pc.b = c.b;
     // Stages this wave has math for: none if its 32 query columns lie beyond the tree; tree
     // rows after its last query are descendants or strangers of all its queries, and those
@@ -556,7 +624,11 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnPar
         float m_blk = -INFINITY;
 #pragma unroll
         for (int r = 0; r < 16; ++r) m_blk = fmaxf(m_blk, sc[r]);
-        m_blk = fmaxf(m_blk, __shfl_xor(m_blk, 32, kWave));
+        {  // the other half of the stage's rows is in the lane 32 away
+          uint32_t lo = __float_as_uint(m_blk), hi = lo;
+          swap_halves(lo, hi);
+          m_blk = fmaxf(__uint_as_float(lo), __uint_as_float(hi));
+        }
         if (__builtin_amdgcn_ballot_w64(m_blk > m_run + tau) != 0) {
           // rare: move the reference.  O must first receive the stage still pending, whose
           // weights are relative to the old reference.
@@ -618,7 +690,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnPar
     // ---- the next piece's queries are requested before this piece's results are stored:
     //      waiting for them later then does not wait for the stores
     const Piece done = pc;
-    cp.advance(map, done.n_st);
+    cp.advance(map, G, done.n_st);
     if (n_acq < n_my) {
       pc = piece_at(cp, n_acq);
       if (pc.n_cmp > 0) load_queries(pc);
@@ -668,17 +740,21 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnPar
 // Finish the units that a range boundary cut: out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s
 // over the workgroups s that hold a piece.  One workgroup per unit, threads mapped to
 // (query, d) exactly as in the main kernel; whole units return at once.
+#ifndef PROPD_COMBINE_CHUNK
+#define PROPD_COMBINE_CHUNK 1
+#endif
 __global__ __launch_bounds__(kAttnThreads) void tree_attn_combine_kernel(AttnParams p, int G) {
+  constexpr int kChunk = PROPD_COMBINE_CHUNK;  // pieces merged per pass
   const int unit = blockIdx.x;
   const int b = unit / p.H, h = unit - b * p.H;
   const StageMap map = {p.B, p.H, p.seq_lens, p.n_nodes, p.L_max, p.T_max};
-  long long n_total = 0, b_start = 0;
-  for (int bb = 0; bb < p.B; ++bb) {
-    if (bb == b) b_start = n_total;
-    n_total += (long long)p.H * map.unit_stages(bb);
-  }
+  const Schedule sch = make_schedule(map, G);
+  if (unit < sch.first_split) return;  // done whole by one workgroup
+  const long long n_total = sch.n_split;
+  if (n_total == 0) return;
   const int us = map.unit_stages(b), T = map.nodes(b);
-  const long long S = b_start + (long long)h * us, E = S + us;
+  const long long S = map.stages_before(b, h) - sch.split_base;  // first stage in the split list
+  const long long E = S + us;
   // workgroup that owns stage x: the largest w with range_start(w) <= x
   auto owner = [&](long long x) {
     long long w = x * G / n_total;
@@ -698,24 +774,44 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_combine_kernel(AttnPar
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[mb][r] = 0.f;
   float M = -INFINITY, lsum = 0.f;
-  for (long long wg = w_first; wg <= w_last; ++wg) {
-    const size_t ps = 2 * (size_t)wg + (range_start(wg, n_total, G) > S ? 0 : 1);
-    const float m = p.part_ml[part_ml_index(ps, wave, 0, lane)];
-    const float l = p.part_ml[part_ml_index(ps, wave, 1, lane)];
-    const float M_new = fmaxf(M, m);
+  // pieces kChunk at a time, so that their loads are independent and in flight together
+  for (long long base = w_first; base <= w_last; base += kChunk) {
+    size_t ps[kChunk];
+    float wgt[kChunk], m[kChunk], l[kChunk];
+    float M_new = M;
+#pragma unroll
+    for (int i = 0; i < kChunk; ++i) {
+      const long long wg = base + i <= w_last ? base + i : w_last;  // surplus slots repeat the last piece
+      ps[i] = 2 * (size_t)wg + (range_start(wg, n_total, G) > S ? 0 : 1);
+      m[i] = p.part_ml[part_ml_index(ps[i], wave, 0, lane)];
+      l[i] = p.part_ml[part_ml_index(ps[i], wave, 1, lane)];
+    }
+#pragma unroll
+    for (int i = 0; i < kChunk; ++i) M_new = fmaxf(M_new, m[i]);
     const float M_safe = M_new == -INFINITY ? 0.f : M_new;
-    const float a_old = fast_exp2(M - M_safe), a_new = fast_exp2(m - M_safe);
-    lsum = lsum * a_old + l * a_new;
+    const float a_old = fast_exp2(M - M_safe);
+    lsum *= a_old;
+#pragma unroll
+    for (int i = 0; i < kChunk; ++i) {
+      wgt[i] = base + i <= w_last ? fast_exp2(m[i] - M_safe) : 0.f;  // ... with weight zero
+      lsum += l[i] * wgt[i];
+    }
     M = M_new;
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
-        const f32x4 o = *reinterpret_cast<const f32x4 *>(p.part_o + part_o_index(ps, wave, 4 * mb + q4, lane));
-        acc[mb][4 * q4] = acc[mb][4 * q4] * a_old + o.x * a_new;
-        acc[mb][4 * q4 + 1] = acc[mb][4 * q4 + 1] * a_old + o.y * a_new;
-        acc[mb][4 * q4 + 2] = acc[mb][4 * q4 + 2] * a_old + o.z * a_new;
-        acc[mb][4 * q4 + 3] = acc[mb][4 * q4 + 3] * a_old + o.w * a_new;
+        f32x4 o[kChunk];
+#pragma unroll
+        for (int i = 0; i < kChunk; ++i)
+          o[i] = *reinterpret_cast<const f32x4 *>(p.part_o + part_o_index(ps[i], wave, 4 * mb + q4, lane));
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          float v = acc[mb][4 * q4 + j] * a_old;
+#pragma unroll
+          for (int i = 0; i < kChunk; ++i) v += o[i][j] * wgt[i];
+          acc[mb][4 * q4 + j] = v;
+        }
       }
   }
   // lanes beyond the tree read unwritten scratch and store nothing; the two lanes of an
