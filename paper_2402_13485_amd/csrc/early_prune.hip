@@ -142,38 +142,42 @@ __global__ __launch_bounds__(kScanThreads) void cu_nodes_kernel(int B,
 // ------------------------------------------------------------------------------------
 // C[m][v] = sum_x A[m][x] * W[v][x].  Both operands are contiguous along x, which is
 // the layout the 32x32x16 MFMA wants (8 consecutive x per lane), so tiles go
-// global -> registers -> LDS -> MFMA operands without any transpose.
-//   - workgroup tile BM x BN, K step 64, four waves in a 2 x 2 arrangement, each
-//     owning (BM/2) x (BN/2) as FM x FN MFMA tiles of 32 x 32;
-//   - LDS is double buffered: one barrier per K step, the step after next is in
-//     flight (in registers) while the current one is multiplied;
+// global -> LDS -> MFMA operands without any transpose.
+//   - workgroup tile 256 x 128, K step 64, eight waves in a 4 x 2 arrangement, each
+//     owning 64 x 64 as 2 x 2 MFMA tiles of 32 x 32;
+//   - K steps stream through a ring of three 48 KB LDS stages filled by direct
+//     global->LDS loads (no staging registers, no LDS stores), two steps ahead of the
+//     math; one barrier per K step.  A row of a stage is 128 bytes (8 chunks of 16); the
+//     lane that fills chunk c of LDS row r fetches chunk c ^ key(r) of the global row, with
+//     key(r) = (r & 7) ^ ((r >> 3) & 1), so that the 16 rows one quarter-wave reads for a
+//     chunk column fall into 16 different bank groups;
+//   - the A rows are gathered through the row table by the loads themselves; rows past
+//     the last one and vocabulary entries past the last re-read the last valid one and
+//     are dropped when the scores are stored;
 //   - the grid is one-dimensional and XCD-aware.  Workgroups are handed to the 8
 //     XCDs round-robin, each XCD has its own L2: workgroup id -> (xcd, slot), and an
 //     XCD walks its own vocabulary tiles with all row tiles of one vocabulary tile
 //     adjacent in time, so a weight tile is fetched from HBM once and hits in that
 //     XCD's L2 for the other row tiles.
-constexpr int kBK = 64, kPitch = kBK + 8;  // pitch 144 B: conflict-free b128 reads
-constexpr int kGemmThreads = 256;
+constexpr int kBK = 64;
+constexpr int kGemmBM = 256, kGemmBN = 128;
+constexpr int kGemmThreads = 512;
+constexpr int kGemmStages = 3;
+constexpr int kGemmRowBytes = kBK * 2;                              // 128
+constexpr int kGemmStageBytes = (kGemmBM + kGemmBN) * kGemmRowBytes;  // 48 KB: A rows, then W rows
+constexpr int kGemmLdsBytes = kGemmStages * kGemmStageBytes;
 constexpr int kXcds = 8;
-#ifndef PROPD_GEMM_BM
-#define PROPD_GEMM_BM 128
-#define PROPD_GEMM_BN 128
-#endif
 
-template <int BM, int BN>
-struct GemmCfg {
-  static constexpr int FM = BM / 64, FN = BN / 64;    // 32x32 tiles per wave
-  static constexpr int LA = BM / 32, LB = BN / 32;    // 16-byte chunks per thread per K step
-  static constexpr int stage_elems = (BM + BN) * kPitch;
-  static constexpr size_t lds_bytes = 2 * (size_t)stage_elems * 2;
-};
+template <int N>
+__device__ __forceinline__ void gemm_wait_vmem() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
 
-template <int BM, int BN>
-__global__ __launch_bounds__(kGemmThreads) void early_head_bf16_kernel(
+__global__ __launch_bounds__(kGemmThreads, 1) void early_head_bf16_kernel(
     int hidden, int vocab, int B, const uint16_t *__restrict__ hidden_states,
     const uint16_t *__restrict__ head_weight, const int32_t *__restrict__ row_src,
     const int32_t *__restrict__ row_base, float *__restrict__ scores, size_t score_pitch) {
-  using C = GemmCfg<BM, BN>;
+  constexpr int BM = kGemmBM, BN = kGemmBN;
   const int m_total = row_base[B];
   const int m_tiles = (m_total + BM - 1) / BM;
   const int n_tiles = (vocab + BN - 1) / BN;
@@ -182,98 +186,117 @@ __global__ __launch_bounds__(kGemmThreads) void early_head_bf16_kernel(
   if (m_tiles == 0 || n_tile >= n_tiles) return;
   const int m0 = (slot % m_tiles) * BM, v0 = n_tile * BN;
 
-  extern __shared__ __attribute__((aligned(16))) unsigned char gemm_smem[];
-  uint16_t *lds = reinterpret_cast<uint16_t *>(gemm_smem);
+  extern __shared__ __attribute__((aligned(1024))) unsigned char gemm_smem[];
+  typedef __attribute__((address_space(3))) void lds_void;
+  typedef const __attribute__((address_space(1))) void global_void;
+  const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_void *)gemm_smem;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
   const int l32 = lane & 31, g = lane >> 5;
 
-  // thread -> (row, 8 columns) of a 32-row slab; LA slabs of A and LB slabs of B per K step
-  const int ld_row = tid >> 3, ld_col = (tid & 7) * 8;
-  const uint16_t *a_ptr[C::LA];
-  const uint16_t *b_ptr[C::LB];
+  // ---- loader: a load instruction fills 8 rows (1 KB).  A stage has 32 such groups of A
+  //      rows and 16 of W rows; wave w takes groups w, w+8, ...: 4 of A and 2 of W.  All of
+  //      a wave's groups have the same parity, so its swizzle key is a per-lane constant.
+  const int ld_sub = lane >> 3;                                        // row within the group
+  const int ld_chunk = ((lane & 7) ^ (ld_sub ^ (wave & 1))) << 4;      // byte offset in the global row
+  const unsigned char *a_src[4], *b_src[2];
 #pragma unroll
-  for (int it = 0; it < C::LA; ++it) {
-    const int m = m0 + it * 32 + ld_row;
-    a_ptr[it] = m < m_total ? hidden_states + (size_t)row_src[m] * hidden + ld_col : nullptr;
+  for (int j = 0; j < 4; ++j) {
+    int m = m0 + 8 * (wave + 8 * j) + ld_sub;
+    m = m < m_total ? m : m_total - 1;
+    a_src[j] = reinterpret_cast<const unsigned char *>(hidden_states + (size_t)row_src[m] * hidden) + ld_chunk;
   }
 #pragma unroll
-  for (int it = 0; it < C::LB; ++it) {
-    const int v = v0 + it * 32 + ld_row;
-    b_ptr[it] = v < vocab ? head_weight + (size_t)v * hidden + ld_col : nullptr;
+  for (int j = 0; j < 2; ++j) {
+    int v = v0 + 8 * (wave + 8 * j) + ld_sub;
+    v = v < vocab ? v : vocab - 1;
+    b_src[j] = reinterpret_cast<const unsigned char *>(head_weight + (size_t)v * hidden) + ld_chunk;
   }
-  const u32x4 zero4 = {0u, 0u, 0u, 0u};
-  u32x4 a_reg[C::LA], b_reg[C::LB];
-  auto fetch = [&](int k0) {
+  auto issue = [&](int sl) {  // the next K step of every source pointer
+    unsigned char *dst = gemm_smem + sl * kGemmStageBytes + wave * 1024;
 #pragma unroll
-    for (int it = 0; it < C::LA; ++it)
-      a_reg[it] = a_ptr[it] ? *reinterpret_cast<const u32x4 *>(a_ptr[it] + k0) : zero4;
+    for (int j = 0; j < 4; ++j) {
+      __builtin_amdgcn_global_load_lds((global_void *)a_src[j], (lds_void *)(dst + j * 8192), 16, 0, 0);
+      a_src[j] += kGemmRowBytes;
+    }
 #pragma unroll
-    for (int it = 0; it < C::LB; ++it)
-      b_reg[it] = b_ptr[it] ? *reinterpret_cast<const u32x4 *>(b_ptr[it] + k0) : zero4;
-  };
-  auto stash = [&](int buf) {
-    uint16_t *As = lds + buf * C::stage_elems;
-    uint16_t *Bs = As + BM * kPitch;
-#pragma unroll
-    for (int it = 0; it < C::LA; ++it)
-      *reinterpret_cast<u32x4 *>(&As[(it * 32 + ld_row) * kPitch + ld_col]) = a_reg[it];
-#pragma unroll
-    for (int it = 0; it < C::LB; ++it)
-      *reinterpret_cast<u32x4 *>(&Bs[(it * 32 + ld_row) * kPitch + ld_col]) = b_reg[it];
+    for (int j = 0; j < 2; ++j) {
+      __builtin_amdgcn_global_load_lds((global_void *)b_src[j],
+                                       (lds_void *)(dst + BM * kGemmRowBytes + j * 8192), 16, 0, 0);
+      b_src[j] += kGemmRowBytes;
+    }
   };
 
-  f32x16 acc[C::FM][C::FN];
+  // ---- per-lane LDS read offsets: operand row l32 of a 32-row block, chunk 2*ks + g
+  uint32_t a_rd[4], b_rd[4];
+  {
+    const int key = (l32 & 7) ^ ((l32 >> 3) & 1);
 #pragma unroll
-  for (int x = 0; x < C::FM; ++x)
+    for (int ks = 0; ks < 4; ++ks) {
+      const int off = l32 * kGemmRowBytes + (((2 * ks + g) ^ key) << 4);
+      a_rd[ks] = smem_base + wm * 64 * kGemmRowBytes + off;
+      b_rd[ks] = smem_base + (BM + wn * 64) * kGemmRowBytes + off;
+    }
+  }
+
+  f32x16 acc[2][2];
 #pragma unroll
-    for (int y = 0; y < C::FN; ++y)
+  for (int x = 0; x < 2; ++x)
+#pragma unroll
+    for (int y = 0; y < 2; ++y)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
 
   const int n_steps = hidden / kBK;
-  fetch(0);
-  stash(0);
-  if (n_steps > 1) fetch(kBK);
-  __syncthreads();
+  int sl_ld = 0, sl = 0;
+#pragma unroll
+  for (int i = 0; i < kGemmStages - 1; ++i)
+    if (i < n_steps) {
+      issue(sl_ld);
+      sl_ld = sl_ld + 1 == kGemmStages ? 0 : sl_ld + 1;
+    }
   for (int step = 0; step < n_steps; ++step) {
-    const int cur = step & 1;
-    if (step + 1 < n_steps) stash(cur ^ 1);
-    if (step + 2 < n_steps) fetch((step + 2) * kBK);
-    const uint16_t *As = lds + cur * C::stage_elems;
-    const uint16_t *Bs = As + BM * kPitch;
+    // step `step` has landed once at most the 6 loads of the step after it are outstanding
+    if (step + 1 < n_steps) gemm_wait_vmem<6>(); else gemm_wait_vmem<0>();
+    __builtin_amdgcn_s_barrier();  // the step is visible; every wave is done with step-1
+    if (step + kGemmStages - 1 < n_steps) {
+      issue(sl_ld);  // refill the slot of step-1
+      sl_ld = sl_ld + 1 == kGemmStages ? 0 : sl_ld + 1;
+    }
+    const uint32_t so = (uint32_t)sl * kGemmStageBytes;
+    sl = sl + 1 == kGemmStages ? 0 : sl + 1;
 #pragma unroll
-    for (int ks = 0; ks < kBK / 16; ++ks) {
-      bf16x8 af[C::FM], bf[C::FN];
+    for (int ks = 0; ks < 4; ++ks) {
+      bf16x8 af[2], bf[2];
 #pragma unroll
-      for (int x = 0; x < C::FM; ++x)
-        af[x] = *reinterpret_cast<const bf16x8 *>(
-            &As[(wm * (BM / 2) + x * 32 + l32) * kPitch + ks * 16 + g * 8]);
+      for (int x = 0; x < 2; ++x)
+        af[x] = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8 *>(
+            (uintptr_t)(a_rd[ks] + so + x * 32 * kGemmRowBytes));
 #pragma unroll
-      for (int y = 0; y < C::FN; ++y)
-        bf[y] = *reinterpret_cast<const bf16x8 *>(
-            &Bs[(wn * (BN / 2) + y * 32 + l32) * kPitch + ks * 16 + g * 8]);
+      for (int y = 0; y < 2; ++y)
+        bf[y] = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8 *>(
+            (uintptr_t)(b_rd[ks] + so + y * 32 * kGemmRowBytes));
 #pragma unroll
-      for (int x = 0; x < C::FM; ++x)
+      for (int x = 0; x < 2; ++x)
 #pragma unroll
-        for (int y = 0; y < C::FN; ++y)
+        for (int y = 0; y < 2; ++y)
           acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[x], bf[y], acc[x][y], 0, 0, 0);
     }
-    __syncthreads();
   }
 
   mfma_settle();
   // accumulator layout of the 32x32 MFMA: lane -> column l32, register r -> row
   // 8*(r/4) + 4*g + r%4
 #pragma unroll
-  for (int x = 0; x < C::FM; ++x)
+  for (int x = 0; x < 2; ++x)
 #pragma unroll
-    for (int y = 0; y < C::FN; ++y) {
-      const int col = v0 + wn * (BN / 2) + y * 32 + l32;
+    for (int y = 0; y < 2; ++y) {
+      const int col = v0 + wn * 64 + y * 32 + l32;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int row = m0 + wm * (BM / 2) + x * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+        const int row = m0 + wm * 64 + x * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
         if (row < m_total && col < vocab) scores[(size_t)row * score_pitch + col] = acc[x][y][r];
       }
     }
@@ -617,12 +640,12 @@ extern "C" propd_status propd_early_prune(
     hipLaunchKernelGGL(row_table_kernel, dim3(1), dim3(kScanThreads), 0, st, B, T_max, ws.n_par,
                        ws.local_list, ws.row_base, ws.row_src);
     if (dt == PROPD_BF16) {
-      constexpr int BM = PROPD_GEMM_BM, BN = PROPD_GEMM_BN;
+      constexpr int BM = kGemmBM, BN = kGemmBN;
       static bool attr_set = false;
       if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&early_head_bf16_kernel<BM, BN>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&early_head_bf16_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)GemmCfg<BM, BN>::lds_bytes) != hipSuccess)
+                                kGemmLdsBytes) != hipSuccess)
           return PROPD_ERR_DEVICE;
         attr_set = true;
       }
@@ -630,10 +653,8 @@ extern "C" propd_status propd_early_prune(
       const long long n_groups = ((vocab + BN - 1) / BN + kXcds - 1) / kXcds;
       const long long grid = kXcds * n_groups * m_tiles_cap;
       if (grid > (1ll << 31) - 1) return PROPD_ERR_UNSUPPORTED;
-      const size_t lds_bytes = GemmCfg<BM, BN>::lds_bytes;
-      auto kern = early_head_bf16_kernel<BM, BN>;
-      hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kGemmThreads), lds_bytes, st, hidden,
-                         vocab, B,
+      hipLaunchKernelGGL(early_head_bf16_kernel, dim3((unsigned)grid), dim3(kGemmThreads),
+                         kGemmLdsBytes, st, hidden, vocab, B,
                          reinterpret_cast<const uint16_t *>(hidden_states),
                          reinterpret_cast<const uint16_t *>(head_weight), ws.row_src, ws.row_base,
                          ws.scores, ws.score_pitch);
