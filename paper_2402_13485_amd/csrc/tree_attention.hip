@@ -51,8 +51,9 @@ struct AttnParams {
   const uint64_t *anc;
   int B, H, T_max, L_max;
   float scale_log2e;
-  float *part_o;   // [2 * grid][128][128]
-  float *part_ml;  // [2 * grid][128][2]
+  float *part_o;   // [2 * grid][4 waves][16 blocks][64 lanes][4]
+  float *part_ml;  // [2 * grid][4 waves][m | l][64 lanes]
+  int32_t *sched;  // [8] the schedule, left by the main kernel for the merge kernel
 };
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -164,6 +165,8 @@ constexpr int kOutRowStores = 8;  // stores per lane of store_out_row
 
 // Partial results keep the register layout, so that a wave writes and reads them as
 // contiguous 1 KB blocks: part_o[slot][wave][4*mb + q4][lane][j], part_ml[slot][wave][m|l][lane].
+constexpr size_t kPartOFloats = 4 * 16 * 64 * 4;  // floats of part_o per slot
+constexpr size_t kPartMlFloats = 4 * 2 * 64;     // floats of part_ml per slot
 __device__ __forceinline__ size_t part_o_index(size_t slot, int wave, int blk, int lane) {
   return (((slot * 4 + wave) * 16 + blk) * 64 + lane) * 4;
 }
@@ -181,8 +184,10 @@ __device__ __forceinline__ size_t part_ml_index(size_t slot, int wave, int which
 //     units (all units when lengths differ, so that every workgroup streams the same number
 //     of rows whatever the mix); a unit cut by a range boundary is finished by the merge
 //     kernel from per-workgroup partial results.
-// A wave-uniform 32-bit load through the scalar cache.  Issued as assembly: the compiler
-// would use a vector load here and wait for it with vmcnt(0), which drains the ring.
+// A wave-uniform 32-bit load on the scalar path.  Issued as assembly: the compiler would
+// use a vector load here and wait for it with vmcnt(0), which drains the ring.  The
+// scalar cache is invalidated when a kernel starts, like the vector caches, so values
+// that an earlier kernel or the caller rewrote in place are seen.
 __device__ __forceinline__ int32_t uniform_load_i32(const int32_t *ptr) {
   const uint64_t a = (uint64_t)(uintptr_t)ptr;
   const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a);
@@ -212,11 +217,59 @@ struct StageMap {
     return (nodes(b) + kStageRows - 1) / kStageRows;
   }
   __device__ __forceinline__ int unit_stages(int b) const { return cache_stages(b) + tree_stages(b); }
+  // the same for a sequence index that differs between lanes (plain loads); 0 past the batch
+  __device__ __forceinline__ int unit_stages_lane(int b) const {
+    if (b >= B) return 0;
+    int L = seq_lens[b], T = n_nodes[b];
+    L = L < 0 ? 0 : (L > L_max ? L_max : L);
+    T = T < 1 ? 1 : (T > T_max ? T_max : T);
+    return (L + kStageRows - 1) / kStageRows + (T + kStageRows - 1) / kStageRows;
+  }
+  // Sequence that holds stage x of the list of all units, and the stages before that
+  // sequence; the last sequence if x lies past the end.  Every lane of the wave takes part:
+  // 64 sequences are sized per pass, with a wave prefix sum.
+  __device__ void locate(long long x, int &b_out, long long &b_start_out) const {
+    const int lane = threadIdx.x & 63;
+    long long base = 0;
+    int b_found = B - 1;
+    long long start_found = 0;
+    bool found = false;
+    for (int b0 = 0; b0 < B && !found; b0 += 64) {
+      const long long mine = (long long)H * unit_stages_lane(b0 + lane);
+      long long incl = mine;  // inclusive prefix over the lanes
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const long long up = __shfl_up(incl, o, kWave);
+        if (lane >= o) incl += up;
+      }
+      const long long excl = base + incl - mine;
+      // the holder is the last sequence that starts at or before x
+      const uint64_t le = __ballot(b0 + lane < B && excl <= x);
+      const int n_le = __popcll(le);
+      const long long total = __shfl(incl, 63, kWave);
+      if (x < base + total || b0 + 64 >= B) {
+        const int src = n_le > 0 ? n_le - 1 : 0;
+        b_found = b0 + src;
+        start_found = __shfl(excl, src, kWave);
+        found = true;
+      }
+      base += total;
+    }
+    b_out = __builtin_amdgcn_readfirstlane(b_found);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)start_found);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)start_found >> 32));
+    b_start_out = (long long)(((uint64_t)hi << 32) | lo);
+  }
   // stages of all units before unit (b, h) in the list of all units
   __device__ long long stages_before(int b, int h) const {
+    const int lane = threadIdx.x & 63;
     long long n = 0;
-    for (int bb = 0; bb < b; ++bb) n += (long long)H * unit_stages(bb);
-    return n + (long long)h * unit_stages(b);
+    for (int b0 = 0; b0 < b; b0 += 64)
+      n += wave_reduce_sum(b0 + lane < b ? (long long)H * unit_stages_lane(b0 + lane) : 0ll);
+    n += (long long)h * unit_stages(b);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)n);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)n >> 32));
+    return (long long)(((uint64_t)hi << 32) | lo);
   }
 };
 
@@ -233,13 +286,22 @@ struct Schedule {
 
 __device__ __forceinline__ Schedule make_schedule(const StageMap &m, long long G) {
   Schedule sc;
+  const int lane = threadIdx.x & 63;
   int us_min = 1 << 30, us_max = 0;
   long long n_all = 0;
-  for (int b = 0; b < m.B; ++b) {
-    const int us = m.unit_stages(b);
-    us_min = us < us_min ? us : us_min;
-    us_max = us > us_max ? us : us_max;
-    n_all += (long long)m.H * us;
+  for (int b0 = 0; b0 < m.B; b0 += 64) {  // 64 sequences per pass, one per lane
+    const bool in = b0 + lane < m.B;
+    const int us = m.unit_stages_lane(b0 + lane);
+    us_min = min(us_min, -wave_reduce_max(in ? -us : -(1 << 30)));
+    us_max = max(us_max, wave_reduce_max(in ? us : 0));
+    n_all += wave_reduce_sum((long long)m.H * us);
+  }
+  us_min = __builtin_amdgcn_readfirstlane(us_min);
+  us_max = __builtin_amdgcn_readfirstlane(us_max);
+  {
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)n_all);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)n_all >> 32));
+    n_all = (long long)(((uint64_t)hi << 32) | lo);
   }
   // whole units first only where they are (nearly) equally long: a workgroup's k of them
   // then differ by at most a few percent between workgroups
@@ -280,12 +342,8 @@ struct Walk {
     int n_my = (int)(range_start(w + 1, sc.n_split, G) - x0);
     // locate stage split_base + x0 of the list of all units
     const long long x = sc.split_base + x0;
-    b = 0;
-    long long b_start = 0;
-    while (b < m.B - 1 && x >= b_start + (long long)m.H * m.unit_stages(b)) {
-      b_start += (long long)m.H * m.unit_stages(b);
-      ++b;
-    }
+    long long b_start;
+    m.locate(x, b, b_start);
     load_sizes(m);
     {
       const int us = cs + ts;
@@ -342,6 +400,13 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnPar
   const StageMap map = {p.B, p.H, p.seq_lens, p.n_nodes, p.L_max, p.T_max};
   const long long G = gridDim.x, w = blockIdx.x;
   const Schedule sch = make_schedule(map, G);
+  if (w == 0 && tid == 0) {  // the merge kernel reads the schedule instead of rebuilding it
+    p.sched[0] = sch.k;
+    p.sched[1] = 0;
+    reinterpret_cast<long long *>(p.sched)[1] = sch.first_split;
+    reinterpret_cast<long long *>(p.sched)[2] = sch.split_base;
+    reinterpret_cast<long long *>(p.sched)[3] = sch.n_split;
+  }
   Walk cp;
   const int n_my = cp.start(map, sch, w, G);
   if (n_my <= 0) return;
@@ -738,21 +803,31 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnPar
 }
 
 // Finish the units that a range boundary cut: out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s
-// over the workgroups s that hold a piece.  One workgroup per unit, threads mapped to
-// (query, d) exactly as in the main kernel; whole units return at once.
-#ifndef PROPD_COMBINE_CHUNK
-#define PROPD_COMBINE_CHUNK 1
-#endif
+// over the workgroups s that hold a piece.  One workgroup per (unit, group of 32 queries);
+// its four waves take four pieces at a time, so that the pieces' loads are in flight
+// together, and hand their scaled parts to wave 0 through LDS.  Lanes map to (query, d)
+// exactly as in the main kernel; whole units return at once.
 __global__ __launch_bounds__(kAttnThreads) void tree_attn_combine_kernel(AttnParams p, int G) {
-  constexpr int kChunk = PROPD_COMBINE_CHUNK;  // pieces merged per pass
-  const int unit = blockIdx.x;
+  const int unit = blockIdx.x >> 2, dw = blockIdx.x & 3;
   const int b = unit / p.H, h = unit - b * p.H;
   const StageMap map = {p.B, p.H, p.seq_lens, p.n_nodes, p.L_max, p.T_max};
-  const Schedule sch = make_schedule(map, G);
+  Schedule sch;  // as the main kernel left it
+  sch.k = uniform_load_i32(p.sched);
+  {
+    auto load64 = [&](int i) {
+      const uint32_t lo = (uint32_t)uniform_load_i32(p.sched + 2 * i);
+      const uint32_t hi = (uint32_t)uniform_load_i32(p.sched + 2 * i + 1);
+      return (long long)(((uint64_t)hi << 32) | lo);
+    };
+    sch.first_split = load64(1);
+    sch.split_base = load64(2);
+    sch.n_split = load64(3);
+  }
   if (unit < sch.first_split) return;  // done whole by one workgroup
   const long long n_total = sch.n_split;
   if (n_total == 0) return;
   const int us = map.unit_stages(b), T = map.nodes(b);
+  if (dw * 32 >= T) return;
   const long long S = map.stages_before(b, h) - sch.split_base;  // first stage in the split list
   const long long E = S + us;
   // workgroup that owns stage x: the largest w with range_start(w) <= x
@@ -765,58 +840,66 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_combine_kernel(AttnPar
   const long long w_first = owner(S), w_last = owner(E - 1);
   if (w_first == w_last) return;  // the unit was finished by one workgroup
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int t = wave * 32 + (lane & 31), g = lane >> 5;
-  if (wave * 32 >= T) return;
-  f32x16 acc[4];
+  __shared__ float s_m[4][64], s_l[4][64];
+  __shared__ f32x4 s_o[3][16][64];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int pw = __builtin_amdgcn_readfirstlane(tid >> 6);  // piece slot of this wave
+  const int t = dw * 32 + (lane & 31), g = lane >> 5;
+  f32x16 acc[4];  // running sums, used by wave 0
 #pragma unroll
   for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[mb][r] = 0.f;
   float M = -INFINITY, lsum = 0.f;
-  // pieces kChunk at a time, so that their loads are independent and in flight together
-  for (long long base = w_first; base <= w_last; base += kChunk) {
-    size_t ps[kChunk];
-    float wgt[kChunk], m[kChunk], l[kChunk];
+  for (long long base = w_first; base <= w_last; base += 4) {
+    const long long wg = base + pw;
+    // short batches leave some workgroups without any stage: they wrote no partial
+    const bool valid = wg <= w_last && range_start(wg + 1, n_total, G) > range_start(wg, n_total, G);
+    float m = -INFINITY, l = 0.f;
+    f32x4 o[16];
+    if (valid) {
+      const size_t ps = 2 * (size_t)wg + (range_start(wg, n_total, G) > S ? 0 : 1);
+      m = p.part_ml[part_ml_index(ps, dw, 0, lane)];
+      l = p.part_ml[part_ml_index(ps, dw, 1, lane)];
+#pragma unroll
+      for (int blk = 0; blk < 16; ++blk)
+        o[blk] = *reinterpret_cast<const f32x4 *>(p.part_o + part_o_index(ps, dw, blk, lane));
+    } else {
+#pragma unroll
+      for (int blk = 0; blk < 16; ++blk) o[blk] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    s_m[pw][lane] = m;
+    s_l[pw][lane] = l;
+    __syncthreads();
     float M_new = M;
 #pragma unroll
-    for (int i = 0; i < kChunk; ++i) {
-      const long long wg = base + i <= w_last ? base + i : w_last;  // surplus slots repeat the last piece
-      ps[i] = 2 * (size_t)wg + (range_start(wg, n_total, G) > S ? 0 : 1);
-      m[i] = p.part_ml[part_ml_index(ps[i], wave, 0, lane)];
-      l[i] = p.part_ml[part_ml_index(ps[i], wave, 1, lane)];
-    }
-#pragma unroll
-    for (int i = 0; i < kChunk; ++i) M_new = fmaxf(M_new, m[i]);
+    for (int i = 0; i < 4; ++i) M_new = fmaxf(M_new, s_m[i][lane]);
     const float M_safe = M_new == -INFINITY ? 0.f : M_new;
-    const float a_old = fast_exp2(M - M_safe);
-    lsum *= a_old;
+    const float wgt = fast_exp2(m - M_safe);  // 0 for an empty slot
+    if (pw > 0) {
 #pragma unroll
-    for (int i = 0; i < kChunk; ++i) {
-      wgt[i] = base + i <= w_last ? fast_exp2(m[i] - M_safe) : 0.f;  // ... with weight zero
-      lsum += l[i] * wgt[i];
+      for (int blk = 0; blk < 16; ++blk) s_o[pw - 1][blk][lane] = o[blk] * wgt;
+    }
+    __syncthreads();
+    if (pw == 0) {
+      const float a_old = fast_exp2(M - M_safe);
+      lsum *= a_old;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) lsum += s_l[i][lane] * fast_exp2(s_m[i][lane] - M_safe);
+#pragma unroll
+      for (int blk = 0; blk < 16; ++blk) {
+        const f32x4 add = o[blk] * wgt + s_o[0][blk][lane] + s_o[1][blk][lane] + s_o[2][blk][lane];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          acc[blk >> 2][4 * (blk & 3) + j] = acc[blk >> 2][4 * (blk & 3) + j] * a_old + add[j];
+      }
     }
     M = M_new;
-#pragma unroll
-    for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        f32x4 o[kChunk];
-#pragma unroll
-        for (int i = 0; i < kChunk; ++i)
-          o[i] = *reinterpret_cast<const f32x4 *>(p.part_o + part_o_index(ps[i], wave, 4 * mb + q4, lane));
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          float v = acc[mb][4 * q4 + j] * a_old;
-#pragma unroll
-          for (int i = 0; i < kChunk; ++i) v += o[i][j] * wgt[i];
-          acc[mb][4 * q4 + j] = v;
-        }
-      }
+    __syncthreads();  // LDS is rewritten by the next four pieces
   }
   // lanes beyond the tree read unwritten scratch and store nothing; the two lanes of an
   // exchange pair hold the same query, so they are active together
-  if (t < T)
+  if (pw == 0 && t < T)
     store_out_row<false>(p.out + ((size_t)unit * p.T_max + t) * kD, acc, 1.f / lsum, g);
 }
 
@@ -915,7 +998,7 @@ static int pick_grid(int B, int H, int L_max, int T_max) {
 // Partial slots: two per workgroup of the grid this call will use.
 size_t tree_attention_workspace_bytes(int B, int H, int L_max, int T_max) {
   const size_t slots = 2 * (size_t)pick_grid(B, H, L_max, T_max);
-  return align_up(slots * 128 * kD * 4, 256) + align_up(slots * 128 * 2 * 4, 256);
+  return align_up(slots * kPartOFloats * 4, 256) + align_up(slots * kPartMlFloats * 4, 256) + 256;
 }
 
 static bool launch_bf16(const AttnParams &p, int grid, int units, hipStream_t st) {
@@ -930,7 +1013,7 @@ static bool launch_bf16(const AttnParams &p, int grid, int units, hipStream_t st
   hipLaunchKernelGGL(tree_attn_bf16_kernel<kRingStages>, dim3((unsigned)grid), dim3(kAttnThreads),
                      lds_bytes, st, p);
   if (!launch_ok()) return false;
-  hipLaunchKernelGGL(tree_attn_combine_kernel, dim3((unsigned)units), dim3(kAttnThreads), 0, st, p,
+  hipLaunchKernelGGL(tree_attn_combine_kernel, dim3((unsigned)units * 4), dim3(kAttnThreads), 0, st, p,
                      grid);
   return launch_ok();
 }
@@ -952,7 +1035,7 @@ extern "C" propd_status propd_tree_attention(const propd_tree *tree, propd_dtype
   if (dt != PROPD_BF16 && dt != PROPD_F32) return PROPD_ERR_INVALID_ARG;
   if (!(scale > 0.f)) return PROPD_ERR_INVALID_ARG;  // the kernels take max before scaling
   const long long units = (long long)tree->B * H;
-  if (units * tree->T_max > (1ll << 30)) return PROPD_ERR_UNSUPPORTED;
+  if (units * tree->T_max > (1ll << 30) || units > (1ll << 28)) return PROPD_ERR_UNSUPPORTED;
   hipStream_t st = as_stream(hip_stream);
 
   if (dt == PROPD_F32) {
@@ -999,7 +1082,10 @@ extern "C" propd_status propd_tree_attention(const propd_tree *tree, propd_dtype
   const size_t slots = 2 * (size_t)grid;
   p.part_o = reinterpret_cast<float *>(workspace);
   p.part_ml = reinterpret_cast<float *>(reinterpret_cast<char *>(workspace) +
-                                        align_up(slots * 128 * kD * 4, 256));
+                                        align_up(slots * kPartOFloats * 4, 256));
+  p.sched = reinterpret_cast<int32_t *>(reinterpret_cast<char *>(workspace) +
+                                        align_up(slots * kPartOFloats * 4, 256) +
+                                        align_up(slots * kPartMlFloats * 4, 256));
   if (!launch_bf16(p, grid, (int)units, st)) return PROPD_ERR_DEVICE;
   return PROPD_OK;
 }

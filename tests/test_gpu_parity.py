@@ -162,6 +162,29 @@ def test_attention_bf16_moving_maximum(pb, oracle, direction):
     check_attention(oracle, x, out, sent)
 
 
+def test_attention_sizes_rewritten_in_place(pb, oracle):
+    """A decoding loop rewrites seq_lens / n_nodes in place between calls and reuses the
+    workspace: every call must see the current sizes (they are read on the scalar path).
+    The second round is so short that some workgroups of the grid get no stage at all."""
+    rng = np.random.default_rng(77)
+    shapes = [synth.rank_product_tree(64, 4), synth.random_tree(rng, 40), synth.chain_tree(9)]
+    x = small_bf16_case(77, 3, 2, 64, shapes, [400, 250, 90], L_max=448)
+    tree = dev_tree(pb, x["n_nodes"], x["parent"])
+    q, kc, vc = to_dev(x["q"]), to_dev(x["k_cache"]), to_dev(x["v_cache"])
+    kt, vt, seq = to_dev(x["k_tree"]), to_dev(x["v_tree"]), to_dev(x["seq_lens"])
+    ws = torch.empty(pb.workspace_bytes(pb.WS_TREE_ATTENTION, 3, 64, 2, 128, 448),
+                     dtype=torch.uint8, device="cuda")
+    for lens, nodes in ([400, 250, 90], [64, 40, 9]), ([33, 250, 0], [17, 40, 1]), ([399, 97, 64], [64, 33, 9]):
+        y = dict(x, seq_lens=np.asarray(lens, np.int32), n_nodes=np.asarray(nodes, np.int32))
+        seq.copy_(to_dev(y["seq_lens"]))          # same device buffers, new contents
+        tree.n_nodes.copy_(to_dev(y["n_nodes"]))
+        sent = sentinel_like(x["q"])
+        out = to_dev(sent)
+        pb.propd_tree_attention(tree, q, kc, vc, kt, vt, seq, x["scale"], out=out, workspace=ws)
+        torch.cuda.synchronize()
+        check_attention(oracle, y, out, sent)
+
+
 def test_attention_survivors_unchanged_by_compaction(pb, oracle):
     """Section 4.1: pruning does not change what a surviving node computes."""
     rng = np.random.default_rng(12)
