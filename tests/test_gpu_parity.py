@@ -370,3 +370,48 @@ def test_whole_step_reduced_c3(pb, oracle):
                                                g(acc["logits"]))
     assert (to_host(alen) == r_len).all() and (to_host(path) == r_path).all()
     assert (to_host(nxt) == r_next).all()
+
+
+# ------------------------------------------------------------------ scratch bounds
+
+
+def test_workspace_bounds_respected(pb, oracle):
+    """Every entry point stays inside the scratch size it asks for: the bytes after
+    propd_workspace_bytes() of a larger buffer keep their fill pattern."""
+    guard = 1 << 16
+
+    def guarded(nbytes):
+        return torch.full((nbytes + guard,), 0xA5, dtype=torch.uint8, device="cuda"), nbytes
+
+    def intact(ws, nbytes):
+        torch.cuda.synchronize()
+        return bool((ws[nbytes:] == 0xA5).all().item())
+
+    rng = np.random.default_rng(5)
+    # attention: a full tree on all four query groups, many splits, and a whole-units case
+    for B, H, T_max, lens, L_max in ((2, 1, 128, [1500, 130], 1536), (3, 2, 64, [300, 77, 0], 320),
+                                     (4, 160, 128, [96, 96, 96, 96], 96)):
+        shapes = [synth.rank_product_tree(T_max, 5 if T_max == 128 else 4)] * B
+        x = small_bf16_case(200 + B, B, H, T_max, shapes, lens, L_max=L_max)
+        tree = dev_tree(pb, x["n_nodes"], x["parent"])
+        ws, n = guarded(pb.workspace_bytes(pb.WS_TREE_ATTENTION, B, T_max, H, 128, L_max))
+        sent = sentinel_like(x["q"])
+        out = to_dev(sent)
+        pb.propd_tree_attention(tree, to_dev(x["q"]), to_dev(x["k_cache"]), to_dev(x["v_cache"]),
+                                to_dev(x["k_tree"]), to_dev(x["v_tree"]), to_dev(x["seq_lens"]),
+                                x["scale"], out=out, workspace=ws)
+        assert intact(ws, n), (B, H, T_max)
+        check_attention(oracle, x, out, sent)
+    # early prune and acceptance
+    w = synth.Workload(95, "case", "bf16", 3, 1, 128, 64, 256, 1000, 5, 1e-3)
+    trees = [synth.rank_product_tree(64, 4), synth.random_tree(rng, 30), synth.chain_tree(7)]
+    xp = synth.make_prune_inputs(w, trees=trees)
+    tree = dev_tree(pb, xp["n_nodes"], xp["parent"], xp["token"])
+    ws, n = guarded(pb.workspace_bytes(pb.WS_EARLY_PRUNE, 3, 64, hidden=256, vocab=1000))
+    pb.propd_early_prune(tree, to_dev(xp["hidden_states"]), to_dev(xp["head_weight"]), 5,
+                         workspace=ws)
+    assert intact(ws, n)
+    acc = synth.make_accept_inputs(w, xp["n_nodes"], xp["parent"], xp["token"])
+    ws, n = guarded(pb.workspace_bytes(pb.WS_ACCEPT_PATH, 3, 64, vocab=1000))
+    pb.propd_accept_path(tree, to_dev(acc["logits"]), workspace=ws)
+    assert intact(ws, n)
