@@ -171,6 +171,24 @@ def main() -> int:
     achieved = alg_bytes / (att_full_ms * 1e-3) / 1e9
     accept_len = to_host(last[0])
 
+    # what a decoding loop does next (outside the metric's step): commit of the accepted path.
+    # Timed on lengths lowered by the path stride so that every accepted row has room; it
+    # overwrites the last rows of the resident cache, which nothing reads after this point.
+    seq_room = torch.clamp(seq - 8, min=0)
+    seq_c = torch.empty_like(seq)
+    kt_acc, vt_acc = (payload_out[2], payload_out[3]) if prune else (kt, vt)
+    t_acc = res0.tree if prune else tree
+    commit_ms = []
+    for _ in range(20):
+        seq_c.copy_(seq_room)
+        e0, e1 = ev(), ev()
+        e0.record()
+        pb.propd_commit_path(t_acc, last[0], last[1], last[2], kt_acc, vt_acc, kc, vc, seq_c)
+        e1.record()
+        torch.cuda.synchronize()
+        commit_ms.append(e0.elapsed_time(e1))
+    commit_us = float(np.median(commit_ms[5:])) * 1e3
+
     result = {
         "metric": "verified tree tokens/s (B*T)",
         "value": sum_T / (ms_per_step * 1e-3),
@@ -185,7 +203,8 @@ def main() -> int:
                    "survivors": int(np.sum(n_kept_host)),
                    "mean_accept_len": float(accept_len.mean())},
         "parts_us": {"attention_full_tree": att_full_ms * 1e3, "early_prune": prune_ms * 1e3,
-                     "attention_compacted_tree": att_small_ms * 1e3, "accept": accept_ms * 1e3},
+                     "attention_compacted_tree": att_small_ms * 1e3, "accept": accept_ms * 1e3,
+                     "commit_outside_step": commit_us},
         "roofline": {"kernel": "propd_tree_attention on the full tree: tree_attn_bf16_kernel "
                                "+ tree_attn_combine_kernel", "bound": "hbm",
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",

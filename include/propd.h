@@ -191,6 +191,39 @@ PROPD_API propd_status propd_accept_path(const propd_tree *tree, propd_dtype dt,
                                int32_t path_stride, int32_t *next_token, void *workspace,
                                size_t workspace_bytes, void *hip_stream);
 
+/*
+ * Commit of the accepted path: what a decoding loop does between acceptance and the next
+ * step (Section 2, "Verification": the longest verified sequence is kept; Section 5.1:
+ * greedy decoding).  With a = accept_len[b] and L = seq_lens[b]:
+ *   - the K/V rows of the accepted nodes accept_path[b,0..a-1] (root first) are copied from
+ *     k_tree / v_tree to rows L..L+a-1 of k_cache / v_cache, for every head;
+ *   - seq_lens[b] becomes L + a;
+ *   - out_tokens[b,0..a-2] are the tokens of the accepted candidates (the path without its
+ *     root, which was emitted by the step before), out_tokens[b,a-1] = next_token[b], the
+ *     rest of the row is -1: the a tokens this step adds to the output, the last of which
+ *     is the next step's root.
+ * If the cache has room for fewer than a rows, only those that fit are copied and
+ * seq_lens[b] stops at L_max; the tokens are still all written.
+ *
+ *   tree        B, T_max, n_nodes and (for out_tokens) token are read
+ *   k_tree,v_tree   [B,H,T_max,d]   dt = PROPD_BF16 or PROPD_F32, d*sizeof a multiple of 16
+ *   k_cache,v_cache [B,H,L_max,d]   in/out; rows outside L..L+a-1 are untouched
+ *   seq_lens    [B]  in/out
+ *   accept_len, accept_path, next_token   as written by propd_accept_path, same path_stride
+ *   out_tokens  [B,out_stride] or NULL; entries beyond out_stride are dropped
+ * Values read from device memory are made safe rather than reported: seq_lens is clamped to
+ * [0, L_max], accept_len to [0, path_stride], and a path entry outside [0, n_nodes[b]) copies
+ * no row (its cache row keeps its contents) and gives token -1.
+ * No workspace.  Data pointers must be 16-byte aligned (PROPD_ERR_INVALID_ARG otherwise).
+ * Must not overlap with a call that reads the same cache or seq_lens.
+ */
+PROPD_API propd_status propd_commit_path(const propd_tree *tree, propd_dtype dt, int32_t H, int32_t d,
+                               const int32_t *accept_len, const int32_t *accept_path,
+                               int32_t path_stride, const int32_t *next_token, const void *k_tree,
+                               const void *v_tree, void *k_cache, void *v_cache, int32_t L_max,
+                               int32_t *seq_lens, int32_t *out_tokens, int32_t out_stride,
+                               void *hip_stream);
+
 /* Workspace size in bytes for one call with these dimensions (arguments a call
  * does not have are ignored).  Pure host arithmetic.  Returns 0 for a bad `which`. */
 typedef enum {

@@ -192,3 +192,25 @@ def accept_path(n_nodes, parent, token, logits, path_stride: Optional[int] = Non
         B, T_max, V, code, _p(n_nodes), _p(parent), _p(token), _p(logits), _p(accept_len),
         _p(path), int(path_stride), _p(next_token)), "accept_path")
     return accept_len, path, next_token
+
+
+def commit_path(n_nodes, token, accept_len, accept_path_, next_token, k_tree, v_tree, k_cache,
+                v_cache, seq_lens, out_stride: Optional[int] = None):
+    """Appends the accepted nodes' K/V rows to copies of the caches.
+    -> (k_cache, v_cache, seq_lens, out_tokens [B,out_stride])"""
+    k_tree, v_tree = np.ascontiguousarray(k_tree), np.ascontiguousarray(v_tree)
+    k_cache, v_cache = np.array(k_cache, copy=True, order="C"), np.array(v_cache, copy=True, order="C")
+    B, H, T_max, d = k_tree.shape
+    L_max = k_cache.shape[2]
+    n_nodes, token = _c(n_nodes, np.int32), _c(token, np.int32)
+    accept_len, path = _c(accept_len, np.int32), _c(accept_path_, np.int32)
+    next_token = _c(next_token, np.int32)
+    seq = np.array(seq_lens, dtype=np.int32, copy=True)
+    if out_stride is None:
+        out_stride = path.shape[1]
+    out = np.empty((B, out_stride), np.int32)
+    _check(lib().propd_oracle_commit_path(
+        B, H, d, T_max, L_max, k_tree.dtype.itemsize, _p(n_nodes), _p(token), _p(accept_len),
+        _p(path), int(path.shape[1]), _p(next_token), _p(k_tree), _p(v_tree), _p(k_cache),
+        _p(v_cache), _p(seq), _p(out), int(out_stride)), "commit_path")
+    return k_cache, v_cache, seq, out

@@ -20,6 +20,8 @@
  *   prune_compact    exhaustive fail patterns on small trees against a set-based
  *                    restatement; mask regenerated from compacted parents
  *   accept_path      simulated greedy autoregressive decoding, brute force over paths
+ *   commit_path      library attention over the committed cache, many-step greedy
+ *                    decoding against plain autoregressive decoding
  *
  * Return value of every function: 0 on success, a positive code on bad input.
  */
@@ -425,6 +427,53 @@ int propd_oracle_accept_path(int32_t B, int32_t T_max, int32_t vocab, int dtype,
       accept_path[(int64_t)b * path_stride + a] = a < np ? path[a] : -1;
     accept_len[b] = np;
     next_token[b] = g[best_node];
+  }
+  return 0;
+}
+
+/*
+ * Commit of the accepted path (Section 2, "Verification": the longest verified
+ * sequence is kept; Section 5.1: greedy decoding).  For every sequence, with
+ * a = accept_len and L = seq_lens: the K/V rows of the a accepted nodes (root
+ * first) become rows L..L+a-1 of the cache of every head, the length becomes
+ * L + a, and the step's a tokens are the tokens of the accepted candidates (the
+ * path without the root) followed by next_token.  Rows that do not fit under
+ * L_max are dropped and the length stops there.
+ *   elem_bytes  bytes of one K/V element (2 or 4); rows are copied as bytes
+ *   out_tokens  [B,out_stride], -1 padded, or NULL
+ */
+int propd_oracle_commit_path(int32_t B, int32_t H, int32_t d, int32_t T_max, int32_t L_max,
+                             int32_t elem_bytes, const int32_t *n_nodes, const int32_t *token,
+                             const int32_t *accept_len, const int32_t *accept_path,
+                             int32_t path_stride, const int32_t *next_token,
+                             const unsigned char *k_tree, const unsigned char *v_tree,
+                             unsigned char *k_cache, unsigned char *v_cache, int32_t *seq_lens,
+                             int32_t *out_tokens, int32_t out_stride) {
+  if (B < 1 || H < 1 || d < 1 || T_max < 1 || L_max < 1 || path_stride < 1) return 1;
+  const int64_t row = (int64_t)d * elem_bytes;
+  for (int32_t b = 0; b < B; ++b) {
+    const int32_t a = accept_len[b], L = seq_lens[b], T = n_nodes[b];
+    if (a < 1 || a > path_stride || L < 0 || L > L_max || T < 1 || T > T_max) return 2;
+    for (int32_t j = 0; j < a; ++j) {
+      const int32_t node = accept_path[(int64_t)b * path_stride + j];
+      if (node < 0 || node >= T) return 3;
+      if (L + j >= L_max) continue; /* no room: dropped */
+      for (int32_t h = 0; h < H; ++h) {
+        const int64_t unit = (int64_t)b * H + h;
+        const int64_t src = (unit * T_max + node) * row, dst = (unit * L_max + L + j) * row;
+        memcpy(k_cache + dst, k_tree + src, (size_t)row);
+        memcpy(v_cache + dst, v_tree + src, (size_t)row);
+      }
+    }
+    seq_lens[b] = L + a > L_max ? L_max : L + a;
+    if (out_tokens) {
+      for (int32_t j = 0; j < out_stride; ++j) {
+        int32_t v = -1;
+        if (j + 1 < a) v = token[(int64_t)b * T_max + accept_path[(int64_t)b * path_stride + j + 1]];
+        else if (j + 1 == a) v = next_token[b];
+        out_tokens[(int64_t)b * out_stride + j] = v;
+      }
+    }
   }
   return 0;
 }

@@ -24,7 +24,7 @@ MAX_TREE = 128
 MAX_PAYLOADS = 8
 
 EXPORTS = ("propd_tree_mask", "propd_tree_attention", "propd_early_prune", "propd_accept_path",
-           "propd_workspace_bytes", "propd_status_string")
+           "propd_commit_path", "propd_workspace_bytes", "propd_status_string")
 
 
 class _Tree(ctypes.Structure):
@@ -70,6 +70,9 @@ def load_library() -> ctypes.CDLL:
     lib.propd_accept_path.restype = ctypes.c_int
     lib.propd_accept_path.argtypes = [ctypes.POINTER(_Tree), ctypes.c_int, i32, vp, vp, vp, i32, vp,
                                       vp, sz, vp]
+    lib.propd_commit_path.restype = ctypes.c_int
+    lib.propd_commit_path.argtypes = [ctypes.POINTER(_Tree), ctypes.c_int, i32, i32, vp, vp, i32, vp,
+                                      vp, vp, vp, vp, i32, vp, vp, i32, vp]
     lib.propd_workspace_bytes.restype = sz
     lib.propd_workspace_bytes.argtypes = [ctypes.c_int, i32, i32, i32, i32, i32, i32, i32]
     lib.propd_status_string.restype = ctypes.c_char_p
@@ -288,3 +291,32 @@ def propd_accept_path(tree: Tree, logits: torch.Tensor, path_stride: Optional[in
         _ptr(next_token), _ptr(ws), ws.numel() * ws.element_size(), _stream()),
         "propd_accept_path")
     return accept_len, path, next_token
+
+
+def propd_commit_path(tree: Tree, accept_len: torch.Tensor, accept_path: torch.Tensor,
+                      next_token: torch.Tensor, k_tree: torch.Tensor, v_tree: torch.Tensor,
+                      k_cache: torch.Tensor, v_cache: torch.Tensor, seq_lens: torch.Tensor,
+                      out_stride: Optional[int] = None) -> torch.Tensor:
+    """Appends the accepted nodes' K/V rows to the caches IN PLACE, advances ``seq_lens`` in
+    place and returns the step's tokens, int32 [B,out_stride], -1 padded."""
+    dt = _dt(k_tree)
+    B, H, T_max, d = k_tree.shape
+    L_max = k_cache.shape[2]
+    for t, name in ((k_tree, "k_tree"), (v_tree, "v_tree"), (k_cache, "k_cache"), (v_cache, "v_cache")):
+        _dev(t, k_tree.dtype, name)
+    for t, name in ((accept_len, "accept_len"), (accept_path, "accept_path"),
+                    (next_token, "next_token"), (seq_lens, "seq_lens")):
+        _dev(t, torch.int32, name)
+    if tuple(v_tree.shape) != (B, H, T_max, d) or tuple(k_cache.shape) != (B, H, L_max, d) or \
+            tuple(v_cache.shape) != (B, H, L_max, d) or tree.B != B or tree.T_max != T_max:
+        raise ValueError("commit_path: tensor shapes disagree")
+    path_stride = accept_path.shape[1]
+    if out_stride is None:
+        out_stride = path_stride
+    out = torch.empty((B, out_stride), dtype=torch.int32, device=k_tree.device)
+    c_tree = tree._c()
+    _check(load_library().propd_commit_path(
+        ctypes.byref(c_tree), dt, H, d, _ptr(accept_len), _ptr(accept_path), path_stride,
+        _ptr(next_token), _ptr(k_tree), _ptr(v_tree), _ptr(k_cache), _ptr(v_cache), L_max,
+        _ptr(seq_lens), _ptr(out), out_stride, _stream()), "propd_commit_path")
+    return out

@@ -39,10 +39,7 @@ constexpr int kStageRows = 32;                 // K/V rows per ring stage
 constexpr int kRowBytes = kD * 2;              // one bf16 row
 constexpr int kHalfStage = kStageRows * kRowBytes;  // K part of a stage; the V part follows
 constexpr int kStageBytes = 2 * kHalfStage;
-#ifndef PROPD_RING_STAGES
-#define PROPD_RING_STAGES 5
-#endif
-constexpr int kRingStages = PROPD_RING_STAGES;  // 16 KB each; two workgroups per CU share 160 KB
+constexpr int kRingStages = 5;  // 16 KB each; two workgroups per CU share 160 KB
 
 struct AttnParams {
   const uint16_t *q, *k_cache, *v_cache, *k_tree, *v_tree;
@@ -96,10 +93,9 @@ __device__ __forceinline__ void wait_vmem() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-// Global loads and stores issued as assembly.  The main kernel keeps its own count of
-// the vector memory operations in flight (they complete in issue order), so that it can
-// wait for a ring stage without also waiting for output stores issued after it; the
-// compiler's own bookkeeping would fence every one of them.  The compiler's hazard
+// Global loads and stores issued as assembly.  The main kernel waits for its vector memory
+// operations itself, with explicit counts; the compiler's own bookkeeping would fence the
+// ring's loads in flight at every use of a loaded register.  The compiler's hazard
 // recognizer does not look inside assembly either: the stores carry their own wait states
 // for data registers written just before by vector or cross-lane instructions, and after
 // themselves, because a store wider than 8 bytes still reads its data registers when the
@@ -114,20 +110,6 @@ __device__ __forceinline__ void global_store16_untracked(void *ptr, u32x4 v) {
 }
 __device__ __forceinline__ void global_store4_untracked(void *ptr, float v) {
   asm volatile("s_nop 7\n\tglobal_store_dword %0, %1, off sc1\n\ts_nop 3" ::"v"(ptr), "v"(v) : "memory");
-}
-
-// wait until at most n of this wave's vector memory operations are outstanding, for a
-// wave-uniform n known only at run time: the largest immediate of the ladder that is <= n
-__device__ __forceinline__ void wait_vmem_upto(int n) {
-  if (n == 4) wait_vmem<4>();
-  else if (n >= 31) wait_vmem<31>();
-  else if (n >= 22) wait_vmem<22>();
-  else if (n >= 21) wait_vmem<21>();
-  else if (n >= 13) wait_vmem<13>();
-  else if (n >= 12) wait_vmem<12>();
-  else if (n >= 8) wait_vmem<8>();
-  else if (n >= 4) wait_vmem<4>();
-  else wait_vmem<0>();
 }
 
 // Exchange between the two 32-lane halves of a wave (v_permlane32_swap): afterwards lane
@@ -161,7 +143,6 @@ __device__ __forceinline__ void store_out_row(uint16_t *orow, const f32x16 (&o)[
       else *reinterpret_cast<u32x4 *>(orow + mb * 32 + 16 * jp + 8 * g) = w4;
     }
 }
-constexpr int kOutRowStores = 8;  // stores per lane of store_out_row
 
 // Partial results keep the register layout, so that a wave writes and reads them as
 // contiguous 1 KB blocks: part_o[slot][wave][4*mb + q4][lane][j], part_ml[slot][wave][m|l][lane].
@@ -490,17 +471,15 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnPar
 
   // ---- ring bookkeeping.  acquire() is called once per stage of the range, in order, by
   //      every wave: it waits for the stage's loads, meets the other waves, and refills the
-  //      slot whose stage every wave finished two acquires ago.  Vector memory operations
-  //      of a wave complete in issue order, so "stage x has landed" is "at most N operations
-  //      outstanding" with N = the number issued after the loads of stage x: those of stage
-  //      x+1, and whatever else (query loads, output stores: vm_a since the last acquire,
-  //      vm_b between the two before) the wave has issued since.
-  static_assert(kAhead == 2, "the operation count below covers the last two acquires");
+  //      slot whose stage every wave finished two acquires ago.  Vector memory loads of a
+  //      wave complete in issue order, so "stage x has landed" is "at most 4 operations
+  //      outstanding": the loads of stage x+1.  Query loads and output stores that the wave
+  //      issued since then are waited for as well (loads and stores are not ordered against
+  //      each other, so the stores cannot be counted off).
+  static_assert(kAhead == 2, "the wait below allows exactly one younger stage in flight");
   int n_acq = 0;              // stages acquired so far
   int slot_acq = 0;           // slot of the next stage to acquire
   int slot_ld = 0;            // slot of the next stage to issue
-  int vm_a = 0, vm_b = 0;     // other vector memory operations issued, see above
-  int q_after = 0;            // operations issued after the pending query loads
   auto next_slot = [](int sl) { return sl + 1 == NS ? 0 : sl + 1; };
 #pragma unroll
   for (int i = 0; i < kAhead; ++i)
@@ -509,15 +488,12 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnPar
       slot_ld = next_slot(slot_ld);
     }
   auto acquire = [&]() -> int {
-    if (n_acq + 1 < n_my) wait_vmem_upto(4 + vm_a + vm_b); else wait_vmem<0>();
+    if (n_acq + 1 < n_my) wait_vmem<4>(); else wait_vmem<0>();
     __builtin_amdgcn_s_barrier();
     if (n_acq + kAhead < n_my) {
       issue(slot_ld);
       slot_ld = next_slot(slot_ld);
-      q_after += 4;
     }
-    vm_b = vm_a;
-    vm_a = 0;
     const int sl = slot_acq;
     slot_acq = next_slot(slot_acq);
     ++n_acq;
@@ -544,12 +520,10 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnPar
     // rows after its last query are descendants or strangers of all its queries, and those
     // stages are the last of the unit.
     pc.n_cmp = 0;
-#ifndef PROPD_TIMING_NO_MATH  // timing experiment: stream only
     if (wave * 32 < c.T) {
       pc.n_cmp = c.cs + wave + 1 - c.s;
       pc.n_cmp = pc.n_cmp > pc.n_st ? pc.n_st : (pc.n_cmp < 0 ? 0 : pc.n_cmp);
     }
-#endif
     return pc;
   };
 
@@ -563,10 +537,6 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnPar
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) qf[ks] = global_load16_untracked(qrow + ks * 16);
     ancv = global_load16_untracked(p.anc + ((size_t)pc.b * p.T_max + tq) * 2);
-#ifdef PROPD_COUNT_QUERY_LOADS
-    vm_a += 9;
-#endif
-    q_after = 0;
   };
   auto wait_queries = [&]() {
     // the registers are named so that their uses cannot be scheduled above the wait
@@ -575,11 +545,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnPar
                         "+v"(qf[6]), "+v"(qf[7]), "+v"(ancv));
     };
     tie();
-#ifdef PROPD_COUNT_QUERY_LOADS
-    wait_vmem_upto(q_after);
-#else
     wait_vmem<0>();
-#endif
     tie();
   };
 
@@ -764,16 +730,10 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnPar
     // ---- write: lane holds d = mb*32 + 8*(r/4) + 4*g + r%4 for its query t
     l_run += __shfl_xor(l_run, 32, kWave);
     m_run *= p.scale_log2e;  // from here on the maximum is in the exponent's (log2) domain
-#ifdef PROPD_TIMING_NO_WRITE  // timing experiment: no output
-    if (wave * 32 < T && l_run == 12345.f) {
-#else
-    if (wave * 32 < T) {  // wave-uniform: the stores below are issued, and counted
-#endif
-      int n_stores;
+    if (wave * 32 < T) {
       if (done.whole) {
         if (t < T)
           store_out_row<true>(p.out + ((size_t)done.unit * p.T_max + t) * kD, o_acc, 1.f / l_run, g);
-        n_stores = kOutRowStores;
       } else {
         // a range starts inside at most one unit and ends inside at most one
         const size_t ps = 2 * (size_t)w + (s0 > 0 ? 0 : 1);
@@ -790,14 +750,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnPar
           global_store4_untracked(p.part_ml + part_ml_index(ps, wave, 0, lane), m_run);
           global_store4_untracked(p.part_ml + part_ml_index(ps, wave, 1, lane), l_run);
         }
-        n_stores = 18;
       }
-#ifdef PROPD_COUNT_STORES
-      vm_a += n_stores;
-      q_after += n_stores;
-#else
-      (void)n_stores;
-#endif
     }
   }
 }

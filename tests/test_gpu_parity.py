@@ -415,3 +415,77 @@ def test_workspace_bounds_respected(pb, oracle):
     ws, n = guarded(pb.workspace_bytes(pb.WS_ACCEPT_PATH, 3, 64, vocab=1000))
     pb.propd_accept_path(tree, to_dev(acc["logits"]), workspace=ws)
     assert intact(ws, n)
+
+
+# ------------------------------------------------------------------ commit of the accepted path
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 24)])
+def test_commit_path_decoding_loop(pb, oracle, dtype, d):
+    """Several steps of acceptance + commit on the GPU, every step against the oracle's, bit for
+    bit: caches (all rows, so untouched ones too), lengths, the step's tokens.  The last steps
+    run into the end of the cache."""
+    import decode_loop_util as dl
+    rng = np.random.default_rng(401)
+    B, H, T_max, L_max, steps = 5, 3, 19, 40, 8
+    prefixes = [[int(t) for t in rng.integers(0, dl.VOCAB, size=n)] for n in (0, 5, 17, 30, 2)]
+    roots = [dl.model_next(p) for p in prefixes]
+    np_dt = np.uint16 if dtype == "bf16" else np.float32
+    kc = sentinel_like(np.zeros((B, H, L_max, d), np_dt))
+    vc = sentinel_like(np.zeros((B, H, L_max, d), np_dt))
+    for b in range(B):
+        kc[b, :, : len(prefixes[b])] = dl.expected_cache_rows(prefixes[b], H, d, 0, dtype)
+        vc[b, :, : len(prefixes[b])] = dl.expected_cache_rows(prefixes[b], H, d, 1, dtype)
+    seq = np.array([len(p) for p in prefixes], np.int32)
+    kc_d, vc_d, seq_d = to_dev(kc), to_dev(vc), to_dev(seq)
+    clipped = False
+    for step in range(steps):
+        n_nodes, parent, token, logits, kt, vt = dl.build_step(rng, prefixes, roots, H, d, T_max, dtype)
+        alen_r, path_r, nxt_r = oracle.accept_path(n_nodes, parent, token, logits, path_stride=T_max)
+        kc, vc, seq_new, out_r = oracle.commit_path(n_nodes, token, alen_r, path_r, nxt_r, kt, vt,
+                                                    kc, vc, seq, out_stride=T_max)
+        tree = dev_tree(pb, n_nodes, parent, token)
+        alen, path, nxt = pb.propd_accept_path(tree, to_dev(logits), path_stride=T_max)
+        out = pb.propd_commit_path(tree, alen, path, nxt, to_dev(kt), to_dev(vt), kc_d, vc_d, seq_d,
+                                   out_stride=T_max)
+        torch.cuda.synchronize()
+        assert (to_host(alen) == alen_r).all() and (to_host(nxt) == nxt_r).all()
+        assert (to_host(out) == out_r).all(), step
+        assert (to_host(seq_d) == seq_new).all(), step
+        assert (to_host(kc_d) == kc).all() and (to_host(vc_d) == vc).all(), step
+        clipped |= bool((seq_new - seq < alen_r).any())
+        for b in range(B):
+            a = int(alen_r[b])
+            toks = [int(t) for t in out_r[b, :a]]
+            prefixes[b] = (prefixes[b] + [roots[b]] + toks[:-1])[: int(seq_new[b])]
+            roots[b] = toks[-1]
+        seq = seq_new
+    assert clipped and (seq == L_max).any()
+
+
+def test_commit_path_bad_indices_write_nothing(pb):
+    """Path entries outside the tree and lengths outside [0, path_stride] come from device memory;
+    they must not turn into accesses outside the tensors."""
+    B, H, T_max, L_max, d = 3, 2, 8, 12, 64
+    shapes = [synth.chain_tree(8), synth.chain_tree(4), synth.chain_tree(8)]
+    n_nodes, parent, _ = synth.pad_trees(shapes, T_max)
+    token = np.arange(B * T_max, dtype=np.int32).reshape(B, T_max)
+    tree = dev_tree(pb, n_nodes, parent, token)
+    kt = np.arange(B * H * T_max * d, dtype=np.float32).reshape(B, H, T_max, d)
+    kc = sentinel_like(np.zeros((B, H, L_max, d), np.float32))
+    kc_d, vc_d = to_dev(kc), to_dev(kc)
+    seq_d = to_dev(np.array([3, 50, -4], np.int32))
+    alen = to_dev(np.array([3, 2, 99], np.int32))
+    path = to_dev(np.array([[0, 77, 2, -1], [0, 5, -1, -1], [0, -3, 2, 3]], np.int32))
+    out = pb.propd_commit_path(tree, alen, path, to_dev(np.array([9, 9, 9], np.int32)), to_dev(kt),
+                               to_dev(-kt), kc_d, vc_d, seq_d, out_stride=4)
+    torch.cuda.synchronize()
+    got = to_host(kc_d)
+    assert to_host(seq_d).tolist() == [6, 12, 4]
+    assert (got[0, :, 3] == kt[0, :, 0]).all() and (got[0, :, 5] == kt[0, :, 2]).all()
+    assert (got[0, :, 4] == kc[0, :, 4]).all() and (got[0, :, 6:] == kc[0, :, 6:]).all()
+    assert (got[1] == kc[1]).all()                       # length past the end: nothing fits
+    assert (got[2, :, 0] == kt[2, :, 0]).all() and (got[2, :, 1] == kc[2, :, 1]).all()
+    assert (got[2, :, 2] == kt[2, :, 2]).all() and (got[2, :, 3] == kt[2, :, 3]).all()
+    assert (got[2, :, 4:] == kc[2, :, 4:]).all()
+    assert to_host(out).tolist() == [[-1, 2, 9, -1], [-1, 9, -1, -1], [-1, 18, 19, 9]]
