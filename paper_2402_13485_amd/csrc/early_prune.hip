@@ -143,14 +143,22 @@ __global__ __launch_bounds__(kScanThreads) void cu_nodes_kernel(int B,
 // C[m][v] = sum_x A[m][x] * W[v][x].  Both operands are contiguous along x, which is
 // the layout the 32x32x16 MFMA wants (8 consecutive x per lane), so tiles go
 // global -> LDS -> MFMA operands without any transpose.
-//   - workgroup tile 256 x 128, K step 64, eight waves in a 4 x 2 arrangement, each
-//     owning 64 x 64 as 2 x 2 MFMA tiles of 32 x 32;
-//   - K steps stream through a ring of three 48 KB LDS stages filled by direct
-//     global->LDS loads (no staging registers, no LDS stores), two steps ahead of the
-//     math; one barrier per K step.  A row of a stage is 128 bytes (8 chunks of 16); the
+//   - workgroup tile 256 rows x 64*FN vocabulary entries with FN = 2, 3 or 4, eight waves
+//     in a 4 x 2 arrangement, each owning 64 x 32*FN as 2 x FN MFMA tiles of 32 x 32.
+//     Wider tiles move fewer operand bytes per FLOP (the kernel is bound by operand
+//     delivery, not by the matrix cores); FN is the width with the fewest
+//     rounds-of-workgroups x width on this chip, computed by every workgroup from the row
+//     count on the device, so the host never needs that count;
+//   - K advances 32 per step through a ring of four 32 KB LDS stages filled by direct
+//     global->LDS loads (no staging registers, no LDS stores), up to three steps ahead of
+//     the math; one barrier per K step.  A row of a stage is 64 bytes (4 chunks of 16); the
 //     lane that fills chunk c of LDS row r fetches chunk c ^ key(r) of the global row, with
-//     key(r) = (r & 7) ^ ((r >> 3) & 1), so that the 16 rows one quarter-wave reads for a
-//     chunk column fall into 16 different bank groups;
+//     key(r) = (r >> 2) & 3, so that the 16 rows one quarter-wave reads for a chunk column
+//     fall into 16 different bank groups;
+//   - operand fragments are double-buffered in registers: the LDS reads of one half step
+//     are issued before the MFMAs of the half step before it, and the barrier sits between
+//     two MFMA groups whose operands are already in registers, so the matrix core has work
+//     queued while waves meet;
 //   - the A rows are gathered through the row table by the loads themselves; rows past
 //     the last one and vocabulary entries past the last re-read the last valid one and
 //     are dropped when the scores are stored;
@@ -159,36 +167,92 @@ __global__ __launch_bounds__(kScanThreads) void cu_nodes_kernel(int B,
 //     XCD walks its own vocabulary tiles with all row tiles of one vocabulary tile
 //     adjacent in time, so a weight tile is fetched from HBM once and hits in that
 //     XCD's L2 for the other row tiles.
-constexpr int kBK = 64;
-constexpr int kGemmBM = 256, kGemmBN = 128;
+constexpr int kBK = 32;
+constexpr int kGemmBM = 256;
+constexpr int kGemmMinFN = 2, kGemmMaxFN = 4;
 constexpr int kGemmThreads = 512;
-constexpr int kGemmStages = 3;
-constexpr int kGemmRowBytes = kBK * 2;                              // 128
-constexpr int kGemmStageBytes = (kGemmBM + kGemmBN) * kGemmRowBytes;  // 48 KB: A rows, then W rows
-constexpr int kGemmLdsBytes = kGemmStages * kGemmStageBytes;
+// ring depth: five stages where they fit into the 160 KB of LDS, four for the widest tile
+__host__ __device__ constexpr int gemm_stages(int fn) { return fn == 4 ? 4 : 5; }
+__host__ __device__ constexpr int gemm_stage_bytes(int fn) { return (256 + 64 * fn) * 64; }
+constexpr int kGemmRowBytes = kBK * 2;                                           // 64
+constexpr int kGemmWOffset = kGemmBM * kGemmRowBytes;                            // W rows follow the A rows
+constexpr int kGemmLdsBytes = 5 * gemm_stage_bytes(3);  // the largest ring: 140 KB (4 x 32 KB for FN = 4)
+static_assert(gemm_stages(4) * gemm_stage_bytes(4) <= kGemmLdsBytes && gemm_stages(2) * gemm_stage_bytes(2) <= kGemmLdsBytes, "ring");
 constexpr int kXcds = 8;
+
+// Tile width (in units of 64 vocabulary entries) for m_tiles row tiles: the time of a
+// launch goes as rounds of workgroups over the compute units times the width; ties go to
+// the wider tile.
+__host__ __device__ inline int gemm_pick_fn(int m_tiles, int vocab, int cus) {
+  int best = kGemmMaxFN;
+  long long best_cost = -1;
+  for (int fn = kGemmMaxFN; fn >= kGemmMinFN; --fn) {
+    const long long n_tiles = (vocab + 64 * fn - 1) / (64 * fn);
+    const long long rounds = (n_tiles * m_tiles + cus - 1) / cus;
+    const long long cost = rounds * fn;
+    if (best_cost < 0 || cost < best_cost) {
+      best = fn;
+      best_cost = cost;
+    }
+  }
+  return best;
+}
 
 template <int N>
 __device__ __forceinline__ void gemm_wait_vmem() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-__global__ __launch_bounds__(kGemmThreads, 1) void early_head_bf16_kernel(
-    int hidden, int vocab, int B, const uint16_t *__restrict__ hidden_states,
-    const uint16_t *__restrict__ head_weight, const int32_t *__restrict__ row_src,
-    const int32_t *__restrict__ row_base, float *__restrict__ scores, size_t score_pitch) {
-  constexpr int BM = kGemmBM, BN = kGemmBN;
-  const int m_total = row_base[B];
-  const int m_tiles = (m_total + BM - 1) / BM;
-  const int n_tiles = (vocab + BN - 1) / BN;
-  const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
-  const int n_tile = (slot / (m_tiles > 0 ? m_tiles : 1)) * kXcds + xcd;
-  if (m_tiles == 0 || n_tile >= n_tiles) return;
-  const int m0 = (slot % m_tiles) * BM, v0 = n_tile * BN;
+// Waits until at most n of this wave's loads are outstanding (n = whole steps of 3 or 4 loads).
+__device__ __forceinline__ void gemm_wait_outstanding(int n) {
+  if (n >= 8) gemm_wait_vmem<8>();
+  else if (n >= 6) gemm_wait_vmem<6>();
+  else if (n >= 4) gemm_wait_vmem<4>();
+  else if (n >= 3) gemm_wait_vmem<3>();
+  else gemm_wait_vmem<0>();
+}
 
-  extern __shared__ __attribute__((aligned(1024))) unsigned char gemm_smem[];
+// LDS read issued as inline assembly so that the wait for it can be placed by hand: the
+// compiler's own placement waits for every outstanding LDS read, also the ones issued ahead
+// for the next half step.  The result is valid only after gemm_wait_frag<>().
+template <int OFFSET>
+__device__ __forceinline__ u32x4 gemm_lds_read16(uint32_t addr) {
+  u32x4 r;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFFSET));
+  return r;
+}
+
+template <int FN>
+struct GemmFrag {
+  u32x4 a[2], b[FN];
+};
+
+// Waits until at most N LDS reads of this wave are outstanding (they return in order); the
+// fragment named is the one waited for, so that its uses stay below the wait.
+template <int N, int FN>
+__device__ __forceinline__ void gemm_wait_frag(GemmFrag<FN> &f) {
+  if constexpr (FN == 2)
+    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(f.a[0]), "+v"(f.a[1]), "+v"(f.b[0]), "+v"(f.b[1]) : "n"(N));
+  else if constexpr (FN == 3)
+    asm volatile("s_waitcnt lgkmcnt(%5)"
+                 : "+v"(f.a[0]), "+v"(f.a[1]), "+v"(f.b[0]), "+v"(f.b[1]), "+v"(f.b[2])
+                 : "n"(N));
+  else
+    asm volatile("s_waitcnt lgkmcnt(%6)"
+                 : "+v"(f.a[0]), "+v"(f.a[1]), "+v"(f.b[0]), "+v"(f.b[1]), "+v"(f.b[2]), "+v"(f.b[3])
+                 : "n"(N));
+}
+
+template <int FN>
+__device__ __forceinline__ void early_head_tile(
+    int hidden, int vocab, int m_total, int m0, int v0, const uint16_t *__restrict__ hidden_states,
+    const uint16_t *__restrict__ head_weight, const int32_t *__restrict__ row_src,
+    float *__restrict__ scores, size_t score_pitch, unsigned char *gemm_smem) {
+  constexpr int BM = kGemmBM, BN = 64 * FN, WN = 32 * FN;
+  constexpr int kStages = gemm_stages(FN), kStageBytes = gemm_stage_bytes(FN);
   typedef __attribute__((address_space(3))) void lds_void;
   typedef const __attribute__((address_space(1))) void global_void;
+  typedef const __attribute__((address_space(3))) bf16x8 lds_frag;
   const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_void *)gemm_smem;
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -196,110 +260,161 @@ __global__ __launch_bounds__(kGemmThreads, 1) void early_head_bf16_kernel(
   const int wm = wave >> 1, wn = wave & 1;
   const int l32 = lane & 31, g = lane >> 5;
 
-  // ---- loader: a load instruction fills 8 rows (1 KB).  A stage has 32 such groups of A
-  //      rows and 16 of W rows; wave w takes groups w, w+8, ...: 4 of A and 2 of W.  All of
-  //      a wave's groups have the same parity, so its swizzle key is a per-lane constant.
-  const int ld_sub = lane >> 3;                                        // row within the group
-  const int ld_chunk = ((lane & 7) ^ (ld_sub ^ (wave & 1))) << 4;      // byte offset in the global row
-  const unsigned char *a_src[4], *b_src[2];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    int m = m0 + 8 * (wave + 8 * j) + ld_sub;
-    m = m < m_total ? m : m_total - 1;
-    a_src[j] = reinterpret_cast<const unsigned char *>(hidden_states + (size_t)row_src[m] * hidden) + ld_chunk;
-  }
+  // ---- loader: a load instruction fills 16 rows (1 KB).  A stage has 16 such groups of A
+  //      rows and 4*FN of W rows; wave w takes groups w and w+8 of each (the second W group
+  //      only where it exists).
+  const int ld_row = lane >> 2;
+  const int ld_chunk = ((lane & 3) ^ ((lane >> 4) & 3)) << 4;  // byte offset in the global row
+  const bool second_w = FN == 4 ? true : (FN == 2 ? false : wave < 4);
+  const int per_step = second_w ? 4 : 3;  // loads of this wave per K step
+  const unsigned char *a_src[2], *b_src[2];
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
-    int v = v0 + 8 * (wave + 8 * j) + ld_sub;
+    int m = m0 + 16 * (wave + 8 * j) + ld_row;
+    m = m < m_total ? m : m_total - 1;
+    a_src[j] = reinterpret_cast<const unsigned char *>(hidden_states + (size_t)row_src[m] * hidden) + ld_chunk;
+    int v = v0 + 16 * (wave + 8 * j) + ld_row;
     v = v < vocab ? v : vocab - 1;
     b_src[j] = reinterpret_cast<const unsigned char *>(head_weight + (size_t)v * hidden) + ld_chunk;
   }
-  auto issue = [&](int sl) {  // the next K step of every source pointer
-    unsigned char *dst = gemm_smem + sl * kGemmStageBytes + wave * 1024;
+  auto issue = [&](int slot) {  // the next K step of every source pointer
+    unsigned char *dst = gemm_smem + slot * kStageBytes + wave * 1024;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < 2; ++j) {
       __builtin_amdgcn_global_load_lds((global_void *)a_src[j], (lds_void *)(dst + j * 8192), 16, 0, 0);
       a_src[j] += kGemmRowBytes;
     }
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      __builtin_amdgcn_global_load_lds((global_void *)b_src[j],
-                                       (lds_void *)(dst + BM * kGemmRowBytes + j * 8192), 16, 0, 0);
-      b_src[j] += kGemmRowBytes;
+    __builtin_amdgcn_global_load_lds((global_void *)b_src[0], (lds_void *)(dst + kGemmWOffset), 16, 0, 0);
+    b_src[0] += kGemmRowBytes;
+    if (second_w) {
+      __builtin_amdgcn_global_load_lds((global_void *)b_src[1], (lds_void *)(dst + kGemmWOffset + 8192), 16, 0, 0);
+      b_src[1] += kGemmRowBytes;
     }
   };
 
   // ---- per-lane LDS read offsets: operand row l32 of a 32-row block, chunk 2*ks + g
-  uint32_t a_rd[4], b_rd[4];
+  uint32_t a_rd[2], b_rd[2];
   {
-    const int key = (l32 & 7) ^ ((l32 >> 3) & 1);
+    const int key = (l32 >> 2) & 3;
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
+    for (int ks = 0; ks < 2; ++ks) {
       const int off = l32 * kGemmRowBytes + (((2 * ks + g) ^ key) << 4);
       a_rd[ks] = smem_base + wm * 64 * kGemmRowBytes + off;
-      b_rd[ks] = smem_base + (BM + wn * 64) * kGemmRowBytes + off;
+      b_rd[ks] = smem_base + kGemmWOffset + wn * WN * kGemmRowBytes + off;
     }
   }
+  typedef GemmFrag<FN> Frag;
+  auto read = [&](Frag &f, uint32_t so, int ks) {
+    const uint32_t pa = a_rd[ks] + so, pb = b_rd[ks] + so;
+    f.a[0] = gemm_lds_read16<0>(pa);
+    f.a[1] = gemm_lds_read16<32 * kGemmRowBytes>(pa);
+    f.b[0] = gemm_lds_read16<0>(pb);
+    f.b[1] = gemm_lds_read16<32 * kGemmRowBytes>(pb);
+    if constexpr (FN >= 3) f.b[2] = gemm_lds_read16<64 * kGemmRowBytes>(pb);
+    if constexpr (FN >= 4) f.b[3] = gemm_lds_read16<96 * kGemmRowBytes>(pb);
+  };
 
-  f32x16 acc[2][2];
+  f32x16 acc[2][FN];
 #pragma unroll
   for (int x = 0; x < 2; ++x)
 #pragma unroll
-    for (int y = 0; y < 2; ++y)
+    for (int y = 0; y < FN; ++y)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
+  auto mma = [&](const Frag &f) {
+#pragma unroll
+    for (int x = 0; x < 2; ++x)
+#pragma unroll
+      for (int y = 0; y < FN; ++y)
+        acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+            __builtin_bit_cast(bf16x8, f.a[x]), __builtin_bit_cast(bf16x8, f.b[y]), acc[x][y], 0, 0, 0);
+  };
 
   const int n_steps = hidden / kBK;
-  int sl_ld = 0, sl = 0;
-#pragma unroll
-  for (int i = 0; i < kGemmStages - 1; ++i)
-    if (i < n_steps) {
-      issue(sl_ld);
-      sl_ld = sl_ld + 1 == kGemmStages ? 0 : sl_ld + 1;
-    }
-  for (int step = 0; step < n_steps; ++step) {
-    // step `step` has landed once at most the 6 loads of the step after it are outstanding
-    if (step + 1 < n_steps) gemm_wait_vmem<6>(); else gemm_wait_vmem<0>();
-    __builtin_amdgcn_s_barrier();  // the step is visible; every wave is done with step-1
-    if (step + kGemmStages - 1 < n_steps) {
-      issue(sl_ld);  // refill the slot of step-1
-      sl_ld = sl_ld + 1 == kGemmStages ? 0 : sl_ld + 1;
-    }
-    const uint32_t so = (uint32_t)sl * kGemmStageBytes;
-    sl = sl + 1 == kGemmStages ? 0 : sl + 1;
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      bf16x8 af[2], bf[2];
-#pragma unroll
-      for (int x = 0; x < 2; ++x)
-        af[x] = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8 *>(
-            (uintptr_t)(a_rd[ks] + so + x * 32 * kGemmRowBytes));
-#pragma unroll
-      for (int y = 0; y < 2; ++y)
-        bf[y] = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8 *>(
-            (uintptr_t)(b_rd[ks] + so + y * 32 * kGemmRowBytes));
-#pragma unroll
-      for (int x = 0; x < 2; ++x)
-#pragma unroll
-        for (int y = 0; y < 2; ++y)
-          acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[x], bf[y], acc[x][y], 0, 0, 0);
-    }
+  // The ring: the step being multiplied, the next one (already landed, its first fragments
+  // are read before this step ends) and kStages-2 steps in flight.
+  const int n_pro = n_steps < kStages - 1 ? n_steps : kStages - 1;
+  int slot_ld = 0;
+  for (int i = 0; i < n_pro; ++i) {
+    issue(slot_ld);
+    slot_ld = slot_ld + 1 == kStages ? 0 : slot_ld + 1;
   }
+  gemm_wait_outstanding((n_pro - 1) * per_step);
+  __builtin_amdgcn_s_barrier();
+  constexpr int kReads = 2 + FN;  // LDS reads of one half step
+  Frag f0, f1;
+  read(f0, 0, 0);
+  uint32_t so = 0;  // byte offset of the stage being multiplied
+  for (int step = 0; step + 1 < n_steps; ++step) {
+    read(f1, so, 1);
+    gemm_wait_frag<kReads>(f0);  // the reads just issued fly while the MFMAs below run
+    mma(f0);
+    __builtin_amdgcn_sched_barrier(0);
+    // the next step has landed once at most the steps after it (kStages-3 of them were
+    // issued) are outstanding
+    {
+      const int issued_after = n_steps - 2 - step < kStages - 3 ? n_steps - 2 - step : kStages - 3;
+      gemm_wait_outstanding(issued_after * per_step);
+    }
+    __builtin_amdgcn_s_barrier();  // it is visible; every wave is done reading step-1
+    if (step + kStages - 1 < n_steps) {
+      issue(slot_ld);  // into the slot of step-1
+      slot_ld = slot_ld + 1 == kStages ? 0 : slot_ld + 1;
+    }
+    so = so + kStageBytes == kStages * kStageBytes ? 0 : so + kStageBytes;
+    read(f0, so, 0);
+    gemm_wait_frag<kReads>(f1);
+    mma(f1);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  read(f1, so, 1);
+  gemm_wait_frag<kReads>(f0);
+  mma(f0);
+  gemm_wait_frag<0>(f1);
+  mma(f1);
 
   mfma_settle();
   // accumulator layout of the 32x32 MFMA: lane -> column l32, register r -> row
   // 8*(r/4) + 4*g + r%4
+  const bool full = m0 + BM <= m_total && v0 + BN <= vocab;
 #pragma unroll
   for (int x = 0; x < 2; ++x)
 #pragma unroll
-    for (int y = 0; y < 2; ++y) {
-      const int col = v0 + wn * 64 + y * 32 + l32;
+    for (int y = 0; y < FN; ++y) {
+      const int col = v0 + wn * WN + y * 32 + l32;
+      const int row0 = m0 + wm * 64 + x * 32 + 4 * g;
+      float *out = scores + (size_t)row0 * score_pitch + col;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int row = m0 + wm * 64 + x * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-        if (row < m_total && col < vocab) scores[(size_t)row * score_pitch + col] = acc[x][y][r];
+        const int dr = 8 * (r >> 2) + (r & 3);
+        if (full || (row0 + dr < m_total && col < vocab)) out[(size_t)dr * score_pitch] = acc[x][y][r];
       }
     }
+}
+
+__global__ __launch_bounds__(kGemmThreads, 1) void early_head_bf16_kernel(
+    int hidden, int vocab, int B, int cus, const uint16_t *__restrict__ hidden_states,
+    const uint16_t *__restrict__ head_weight, const int32_t *__restrict__ row_src,
+    const int32_t *__restrict__ row_base, float *__restrict__ scores, size_t score_pitch) {
+  const int m_total = row_base[B];
+  const int m_tiles = (m_total + kGemmBM - 1) / kGemmBM;
+  if (m_tiles == 0) return;
+  const int fn = gemm_pick_fn(m_tiles, vocab, cus);
+  const int n_tiles = (vocab + 64 * fn - 1) / (64 * fn);
+  const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+  const int n_tile = (slot / m_tiles) * kXcds + xcd;
+  if (n_tile >= n_tiles) return;
+  const int m0 = (slot % m_tiles) * kGemmBM, v0 = n_tile * 64 * fn;
+  extern __shared__ __attribute__((aligned(1024))) unsigned char gemm_smem[];
+  if (fn == 2)
+    early_head_tile<2>(hidden, vocab, m_total, m0, v0, hidden_states, head_weight, row_src, scores,
+                       score_pitch, gemm_smem);
+  else if (fn == 3)
+    early_head_tile<3>(hidden, vocab, m_total, m0, v0, hidden_states, head_weight, row_src, scores,
+                       score_pitch, gemm_smem);
+  else
+    early_head_tile<4>(hidden, vocab, m_total, m0, v0, hidden_states, head_weight, row_src, scores,
+                       score_pitch, gemm_smem);
 }
 
 // fp32 variant: one score per thread, a plain sequential dot product.
@@ -573,6 +688,18 @@ __global__ void fill_rank_kernel(int n, int T_max, const int32_t *__restrict__ n
 
 }  // namespace propd
 
+static int prune_compute_units() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+      cus = prop.multiProcessorCount;
+    if (cus <= 0) cus = 256;
+  }
+  return cus;
+}
+
 extern "C" propd_status propd_early_prune(
     const propd_tree *tree, propd_dtype dt, int32_t hidden, int32_t vocab, int32_t top_k,
     const void *hidden_states, const void *head_weight, uint64_t *keep_bits, int32_t *new_index,
@@ -640,7 +767,7 @@ extern "C" propd_status propd_early_prune(
     hipLaunchKernelGGL(row_table_kernel, dim3(1), dim3(kScanThreads), 0, st, B, T_max, ws.n_par,
                        ws.local_list, ws.row_base, ws.row_src);
     if (dt == PROPD_BF16) {
-      constexpr int BM = kGemmBM, BN = kGemmBN;
+      constexpr int BM = kGemmBM, BN = 64 * kGemmMinFN;  // the grid covers the narrowest tiles
       static bool attr_set = false;
       if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(&early_head_bf16_kernel),
@@ -654,7 +781,7 @@ extern "C" propd_status propd_early_prune(
       const long long grid = kXcds * n_groups * m_tiles_cap;
       if (grid > (1ll << 31) - 1) return PROPD_ERR_UNSUPPORTED;
       hipLaunchKernelGGL(early_head_bf16_kernel, dim3((unsigned)grid), dim3(kGemmThreads),
-                         kGemmLdsBytes, st, hidden, vocab, B,
+                         kGemmLdsBytes, st, hidden, vocab, B, prune_compute_units(),
                          reinterpret_cast<const uint16_t *>(hidden_states),
                          reinterpret_cast<const uint16_t *>(head_weight), ws.row_src, ws.row_base,
                          ws.scores, ws.score_pitch);
