@@ -53,39 +53,11 @@ def build_inputs(w, synth):
     return att, pr, acc, token
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", type=int, default=4, choices=[2, 3, 4, 5])
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-seconds", type=float, default=15.0,
-                    help="CPU work the oracle baseline is bounded to (whole sequences)")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="run only a plain 1 GiB device copy (the reference kernel that the "
-                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by)")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU; nothing here uses a second one "
-              "(sequences and heads shard with no exchange, see DESIGN.md). Use --gpus 1.",
-              file=sys.stderr)
-        return 2
-
-    import torch
-    from paper_2402_13485_amd import binding as pb
-    from paper_2402_13485_amd import synth
+def resident_step(w, att, pr, acc, token, torch, pb):
+    """Uploads one workload's inputs (they stay resident) and returns a namespace holding
+    `step(marks=None)`, one pass of the hot path, and the tensors it works on."""
+    import types
     to_dev, to_host = pb.to_device, pb.to_host
-
-    pb.load_library()  # fails loudly if the HIP library is not built
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        return 2
-    torch.cuda.set_device(0)
-    if args.copy_calibration:
-        return copy_calibration(torch)
-    w = synth.WORKLOADS[args.workload]
-    att, pr, acc, token = build_inputs(w, synth)
     B, H, d, T_max, L_max = att["B"], att["H"], att["d"], att["T_max"], att["L_max"]
 
     # ---- upload; everything below stays resident
@@ -150,6 +122,55 @@ def main() -> int:
         if marks is not None:
             marks.append(m)
         return r
+
+    return types.SimpleNamespace(**locals())
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", type=int, default=4, choices=[2, 3, 4, 5])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0,
+                    help="CPU work the oracle baseline is bounded to (whole sequences)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a plain 1 GiB device copy (the reference kernel that the "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by)")
+    ap.add_argument("--tree-size-table", action="store_true",
+                    help="instead of the benchmark line: time the step at tree sizes 16..128 of "
+                         "this workload's shape, feed the times to the library's tree-size "
+                         "controller and print its estimates and its choice")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; nothing here uses a second one "
+              "(sequences and heads shard with no exchange, see DESIGN.md). Use --gpus 1.",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2402_13485_amd import binding as pb
+    from paper_2402_13485_amd import synth
+    to_dev, to_host = pb.to_device, pb.to_host
+
+    pb.load_library()  # fails loudly if the HIP library is not built
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    if args.copy_calibration:
+        return copy_calibration(torch)
+    w = synth.WORKLOADS[args.workload]
+    if args.tree_size_table:
+        return tree_size_table(w, args, torch, pb, synth)
+    att, pr, acc, token = build_inputs(w, synth)
+    S = resident_step(w, att, pr, acc, token, torch, pb)
+    B, H, d, T_max, L_max = S.B, S.H, S.d, S.T_max, S.L_max
+    step, prune, seq, kc, vc, kt, vt, tree, ev = S.step, S.prune, S.seq, S.kc, S.vc, S.kt, S.vt, S.tree, S.ev
+    n_kept_host = S.n_kept_host
+    if prune:
+        payload_out, res0 = S.payload_out, S.res0
 
     for _ in range(args.warmup):
         step()
@@ -220,6 +241,54 @@ def main() -> int:
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, att, pr, acc, token, args.cpu_seconds)
     print(json.dumps(result), flush=True)
+    return 0
+
+
+# Stand-in for measured head accuracies (no trained heads exist here): top-1 accuracy of head h
+# falls with its distance from the last verified token, and the top-k frequency grows with
+# log k.  Five heads (the deepest synthetic tree has depth 5), ten candidates per head.
+HEAD_TOP1 = (0.60, 0.42, 0.30, 0.22, 0.16)
+HEAD_K_MAX = 10
+
+
+def synthetic_hit_rates():
+    k = np.arange(1, HEAD_K_MAX + 1, dtype=np.float64)
+    return np.array([np.minimum(0.95, a * (1.0 + 0.35 * np.log(k))) for a in HEAD_TOP1])
+
+
+def tree_size_table(w, args, torch, pb, synth):
+    """Section 4.2 on measured times: the step is timed at each candidate tree size on this
+    workload's shape, the controller fits time against size, estimates the accepted length of
+    its best tree of each size from the (synthetic) head accuracies and picks the size."""
+    import dataclasses
+    sizes = [16, 32, 64, 96, 128]
+    ctl = pb.Controller(sizes, len(HEAD_TOP1), HEAD_K_MAX, alpha=0.5, lam=0.05,
+                        hit_rate_init=synthetic_hit_rates())
+    ms = []
+    for n, T in enumerate(sizes):
+        wt = dataclasses.replace(w, T_max=T)
+        att, pr, acc, token = build_inputs(wt, synth)
+        S = resident_step(wt, att, pr, acc, token, torch, pb)
+        for _ in range(args.warmup):
+            S.step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            S.step()
+        torch.cuda.synchronize()
+        ms.append((time.perf_counter() - t0) * 1e3 / args.steps)
+        ctl.observe_time(T, ms[-1], now=float(n))
+        log(f"tree size {T}: {ms[-1]:.3f} ms per step, survivors {int(np.sum(S.n_kept_host))}")
+        del S, att, pr, acc
+        torch.cuda.empty_cache()
+    best, speed, (b0, b1) = ctl.best_size(now=float(len(sizes)))
+    lens = [ctl.build_tree(T)["expected_len"] for T in sizes]
+    out = {"mode": "tree_size_table", "workload": w.name, "B": w.B, "sizes": sizes,
+           "ms_per_step": ms, "beta0_ms": b0, "beta1_ms_per_node": b1,
+           "t_est_ms": [b0 + b1 * T for T in sizes], "expected_accept_len": lens,
+           "accepted_tokens_per_ms": [float(x) for x in speed], "best_size": best,
+           "head_accuracies": "synthetic", "steps": args.steps, "warmup": args.warmup}
+    print(json.dumps(out), flush=True)
     return 0
 
 

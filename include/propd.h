@@ -224,6 +224,66 @@ PROPD_API propd_status propd_commit_path(const propd_tree *tree, propd_dtype dt,
                                int32_t *seq_lens, int32_t *out_tokens, int32_t out_stride,
                                void *hip_stream);
 
+/*
+ * Dynamic token-tree generation (Section 4.2): the controller that picks the tree size from
+ * measured iteration times and measured head accuracies.  HOST code: every pointer below is
+ * a host pointer, nothing is enqueued on a stream, no device is touched.  It is meant to run
+ * now and then between decoding steps (Section 4.2.3), not every step.
+ *
+ * State lives in caller-owned host memory of propd_controller_bytes() bytes, 8-byte aligned,
+ * set up once by propd_controller_init(); a state that was not initialised is rejected with
+ * PROPD_ERR_INVALID_ARG.  Calls on one state must not overlap.
+ *
+ *   sizes        [n_sizes] the candidate tree sizes S (root included), strictly rising,
+ *                1 <= size <= PROPD_MAX_TREE
+ *   n_heads      number of prediction heads; head i proposes the token i+1 places after the root
+ *   k_max        candidates per head that the statistics cover
+ *   alpha        weight of a new sample in every running mean, 0 < alpha <= 1
+ *   lambda       decay of the regression weight with the age of a mean, W = exp(-lambda * age),
+ *                in units of 1/`now`
+ *   hit_rate_init [n_heads*k_max] or NULL: starting values of P_i^k (frequency of "the true token
+ *                is within the top-k of head i", k = 1..k_max), rising in k, within [0,1];
+ *                NULL = zeros
+ *
+ * observe_time   Section 4.2.1: T_perf^size <- (1-alpha) T_perf^size + alpha t (the first
+ *                sample of a size starts its mean), and its age restarts at `now`.  `size`
+ *                must be one of S.  `now` is the caller's clock in any unit (steps, seconds).
+ * observe_hit    Section 4.2.2: P_head^k <- (1-alpha) P_head^k + alpha [rank < k] for every k;
+ *                `rank` is the 0-based position of the token that was finally decoded in
+ *                that head's candidate list, negative (or >= k_max) when it was not in it.
+ * fit            Section 4.2.1: beta0, beta1 minimising sum_i W_i (T_perf^i - beta0 - beta1 i)^2
+ *                over the sizes seen so far, closed form.  One size seen: beta1 = 0.  None:
+ *                PROPD_ERR_UNSUPPORTED.
+ * build_tree     Section 4.2.2: the tree of `size` nodes with the largest estimated acceptance
+ *                length, root first, every parent before its children:
+ *                  parent[i]  index of the parent (-1 for the root)
+ *                  depth[i]   0 for the root; a node at depth d comes from head d-1
+ *                  choice[i]  0-based rank of the node's token in its head's list (-1 root)
+ *                  node_value[i]  product of the accuracies p_j^(k_j) along its path (root 1)
+ *                  *expected_len  sum of the node values
+ *                  *n_built   nodes written: `size`, or fewer when the heads have no more
+ *                             candidates (n_heads levels of k_max each)
+ *                Output arrays hold `size` entries; any of them may be NULL except n_built.
+ *                Equal values: the shallower node first, then the earlier parent, then the
+ *                lower rank.
+ * best_size      Section 4.2.3: speed[j] = l(sizes[j]) / T_est^(sizes[j]) for every candidate
+ *                size (0 where the estimated time is not positive), *best_size = the size
+ *                with the largest speed (the smaller one on a tie); speed, beta0, beta1 may
+ *                be NULL.
+ */
+PROPD_API size_t propd_controller_bytes(int32_t n_sizes, int32_t n_heads, int32_t k_max);
+PROPD_API propd_status propd_controller_init(void *state, size_t state_bytes, const int32_t *sizes,
+                               int32_t n_sizes, int32_t n_heads, int32_t k_max, double alpha,
+                               double lambda, const double *hit_rate_init);
+PROPD_API propd_status propd_controller_observe_time(void *state, int32_t size, double t, double now);
+PROPD_API propd_status propd_controller_observe_hit(void *state, int32_t head, int32_t rank);
+PROPD_API propd_status propd_controller_fit(const void *state, double now, double *beta0, double *beta1);
+PROPD_API propd_status propd_controller_build_tree(const void *state, int32_t size, int32_t *n_built,
+                               int32_t *parent, int32_t *depth, int32_t *choice,
+                               double *node_value, double *expected_len);
+PROPD_API propd_status propd_controller_best_size(const void *state, double now, int32_t *best_size,
+                               double *speed, double *beta0, double *beta1);
+
 /* Workspace size in bytes for one call with these dimensions (arguments a call
  * does not have are ignored).  Pure host arithmetic.  Returns 0 for a bad `which`. */
 typedef enum {

@@ -24,7 +24,10 @@ MAX_TREE = 128
 MAX_PAYLOADS = 8
 
 EXPORTS = ("propd_tree_mask", "propd_tree_attention", "propd_early_prune", "propd_accept_path",
-           "propd_commit_path", "propd_workspace_bytes", "propd_status_string")
+           "propd_commit_path", "propd_workspace_bytes", "propd_status_string",
+           "propd_controller_bytes", "propd_controller_init", "propd_controller_observe_time",
+           "propd_controller_observe_hit", "propd_controller_fit", "propd_controller_build_tree",
+           "propd_controller_best_size")
 
 
 class _Tree(ctypes.Structure):
@@ -75,6 +78,21 @@ def load_library() -> ctypes.CDLL:
                                       vp, vp, vp, vp, i32, vp, vp, i32, vp]
     lib.propd_workspace_bytes.restype = sz
     lib.propd_workspace_bytes.argtypes = [ctypes.c_int, i32, i32, i32, i32, i32, i32, i32]
+    dbl, pd = ctypes.c_double, ctypes.POINTER(ctypes.c_double)
+    lib.propd_controller_bytes.restype = sz
+    lib.propd_controller_bytes.argtypes = [i32, i32, i32]
+    lib.propd_controller_init.restype = ctypes.c_int
+    lib.propd_controller_init.argtypes = [vp, sz, vp, i32, i32, i32, dbl, dbl, vp]
+    lib.propd_controller_observe_time.restype = ctypes.c_int
+    lib.propd_controller_observe_time.argtypes = [vp, i32, dbl, dbl]
+    lib.propd_controller_observe_hit.restype = ctypes.c_int
+    lib.propd_controller_observe_hit.argtypes = [vp, i32, i32]
+    lib.propd_controller_fit.restype = ctypes.c_int
+    lib.propd_controller_fit.argtypes = [vp, dbl, pd, pd]
+    lib.propd_controller_build_tree.restype = ctypes.c_int
+    lib.propd_controller_build_tree.argtypes = [vp, i32, ctypes.POINTER(i32), vp, vp, vp, vp, pd]
+    lib.propd_controller_best_size.restype = ctypes.c_int
+    lib.propd_controller_best_size.argtypes = [vp, dbl, ctypes.POINTER(i32), vp, pd, pd]
     lib.propd_status_string.restype = ctypes.c_char_p
     lib.propd_status_string.argtypes = [ctypes.c_int]
     _lib = lib
@@ -320,3 +338,62 @@ def propd_commit_path(tree: Tree, accept_len: torch.Tensor, accept_path: torch.T
         _ptr(next_token), _ptr(k_tree), _ptr(v_tree), _ptr(k_cache), _ptr(v_cache), L_max,
         _ptr(seq_lens), _ptr(out), out_stride, _stream()), "propd_commit_path")
     return out
+
+
+class Controller:
+    """Host-side tree-size controller (``propd_controller_*``).  The state is a numpy buffer this
+    object owns; every method is one C call with host arrays."""
+
+    def __init__(self, sizes, n_heads: int, k_max: int, alpha: float, lam: float,
+                 hit_rate_init=None):
+        lib = load_library()
+        self.sizes = np.ascontiguousarray(sizes, dtype=np.int32)
+        self.n_heads, self.k_max = int(n_heads), int(k_max)
+        nbytes = lib.propd_controller_bytes(len(self.sizes), n_heads, k_max)
+        if nbytes == 0:
+            raise ValueError("controller: dimensions out of range")
+        self._state = np.zeros(nbytes // 8 + 1, dtype=np.float64)  # 8-byte aligned
+        init = None
+        if hit_rate_init is not None:
+            init = np.ascontiguousarray(hit_rate_init, dtype=np.float64).reshape(n_heads, k_max)
+        _check(lib.propd_controller_init(self._state.ctypes.data, self._state.nbytes,
+                                         self.sizes.ctypes.data, len(self.sizes), n_heads, k_max,
+                                         alpha, lam, None if init is None else init.ctypes.data),
+               "propd_controller_init")
+
+    def observe_time(self, size: int, t: float, now: float) -> None:
+        _check(load_library().propd_controller_observe_time(self._state.ctypes.data, size, t, now),
+               "propd_controller_observe_time")
+
+    def observe_hit(self, head: int, rank: int) -> None:
+        _check(load_library().propd_controller_observe_hit(self._state.ctypes.data, head, rank),
+               "propd_controller_observe_hit")
+
+    def fit(self, now: float):
+        b0, b1 = ctypes.c_double(), ctypes.c_double()
+        _check(load_library().propd_controller_fit(self._state.ctypes.data, now, ctypes.byref(b0),
+                                                   ctypes.byref(b1)), "propd_controller_fit")
+        return b0.value, b1.value
+
+    def build_tree(self, size: int):
+        """-> dict(parent, depth, choice int32 [n], node_value float64 [n], expected_len)"""
+        n = ctypes.c_int32()
+        parent, depth, choice = (np.full(size, -9, np.int32) for _ in range(3))
+        value = np.zeros(size, np.float64)
+        total = ctypes.c_double()
+        _check(load_library().propd_controller_build_tree(
+            self._state.ctypes.data, size, ctypes.byref(n), parent.ctypes.data, depth.ctypes.data,
+            choice.ctypes.data, value.ctypes.data, ctypes.byref(total)), "propd_controller_build_tree")
+        k = n.value
+        return dict(parent=parent[:k], depth=depth[:k], choice=choice[:k], node_value=value[:k],
+                    expected_len=total.value)
+
+    def best_size(self, now: float):
+        """-> (best size, speed per candidate size, (beta0, beta1))"""
+        best = ctypes.c_int32()
+        speed = np.zeros(len(self.sizes), np.float64)
+        b0, b1 = ctypes.c_double(), ctypes.c_double()
+        _check(load_library().propd_controller_best_size(
+            self._state.ctypes.data, now, ctypes.byref(best), speed.ctypes.data, ctypes.byref(b0),
+            ctypes.byref(b1)), "propd_controller_best_size")
+        return best.value, speed, (b0.value, b1.value)

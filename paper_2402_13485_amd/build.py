@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libpropd.so")
 SOURCES = ["tree_mask.hip", "tree_attention.hip", "early_prune.hip", "accept_path.hip",
-           "commit_path.hip"]
+           "commit_path.hip", "tree_controller.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",  # no packed-fp32 codegen

@@ -252,7 +252,6 @@ __device__ __forceinline__ void early_head_tile(
   constexpr int kStages = gemm_stages(FN), kStageBytes = gemm_stage_bytes(FN);
   typedef __attribute__((address_space(3))) void lds_void;
   typedef const __attribute__((address_space(1))) void global_void;
-  typedef const __attribute__((address_space(3))) bf16x8 lds_frag;
   const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_void *)gemm_smem;
 
   const int tid = threadIdx.x, lane = tid & 63;
