@@ -140,6 +140,49 @@ def early_head_rank(n_nodes, parent, token, hidden_states, head_weight, top_k):
     return rank, margin
 
 
+def early_head_logprob(n_nodes, parent, token, hidden_states, head_weight):
+    """-> (logq, logm) float64 [B,T_max]: log of the head's predicted probability of every node's
+    token given its parent, and its sum along the root path (the sequence's log marginal)."""
+    hidden_states = np.ascontiguousarray(hidden_states)
+    head_weight = np.ascontiguousarray(head_weight)
+    code = _dtype_code(hidden_states)
+    if head_weight.dtype != hidden_states.dtype:
+        raise TypeError("mixed tensor dtypes")
+    B, T_max, Hd = hidden_states.shape
+    V = head_weight.shape[0]
+    assert head_weight.shape == (V, Hd)
+    n_nodes, parent, token = _c(n_nodes, np.int32), _c(parent, np.int32), _c(token, np.int32)
+    logq = np.empty((B, T_max), dtype=np.float64)
+    logm = np.empty((B, T_max), dtype=np.float64)
+    _check(lib().propd_oracle_early_head_logprob(
+        B, T_max, Hd, V, code, _p(n_nodes), _p(parent), _p(token), _p(hidden_states),
+        _p(head_weight), _p(logq), _p(logm)), "early_head_logprob")
+    return logq, logm
+
+
+def prob_fail_flags(n_nodes, logm, threshold=None, keep_count=None):
+    """The probability-based decision (Section 4.1): a sequence goes when its marginal is below
+    `threshold`, or (keep_count given) when it is not among the `keep_count` most probable
+    sequences of its tree (equal marginals: the lower node index first).  Returns an int32
+    [B,T_max] array, 1 = pruned by the criterion, 0 = kept; the root is always 0.  Shaped as a
+    `rank` for prune_compact(..., top_k=1), which then removes what hangs below a pruned node
+    (nothing more: marginals never grow along a path)."""
+    logm = np.asarray(logm, np.float64)
+    B, T_max = logm.shape
+    fail = np.zeros((B, T_max), np.int32)
+    log_thr = -np.inf if not threshold else float(np.log(threshold))
+    for b in range(B):
+        T = int(n_nodes[b])
+        for i in range(1, T):
+            if keep_count is None:
+                fail[b, i] = 0 if logm[b, i] >= log_thr else 1
+            else:
+                ahead = sum(1 for j in range(T)
+                            if logm[b, j] > logm[b, i] or (logm[b, j] == logm[b, i] and j < i))
+                fail[b, i] = 0 if ahead < keep_count else 1
+    return fail
+
+
 def prune_compact(n_nodes, parent, token, rank, top_k):
     """-> dict with keep_bits, new_index, orig_index, n_kept, cu_nodes and the compacted tree."""
     n_nodes, parent = _c(n_nodes, np.int32), _c(parent, np.int32)

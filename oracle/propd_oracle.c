@@ -277,6 +277,71 @@ int propd_oracle_early_head_rank(int32_t B, int32_t T_max, int32_t hidden, int32
 }
 
 /*
+ * Probability-based selection (Section 4.1, "Pruning Criterion", the second criterion): the
+ * early head's scores are turned into predicted probabilities, q_c = softmax(z_p)[tok_c] for
+ * a child c of p, and a candidate sequence gets the marginal probability of its tokens, the
+ * product of q along its root path.  In logarithms:
+ *   logq[c]   = z_p[tok_c] - log sum_v exp(z_p[v])        (0 for the root)
+ *   logm[c]   = logm[parent(c)] + logq[c]                  (0 for the root)
+ * Both [B,T_max]; padding entries are set to 0 and carry no meaning.
+ * The decisions themselves (threshold or rank over logm) are taken by the caller.
+ */
+int propd_oracle_early_head_logprob(int32_t B, int32_t T_max, int32_t hidden, int32_t vocab,
+                                    int dtype, const int32_t *n_nodes, const int32_t *parent,
+                                    const int32_t *token, const void *hidden_states,
+                                    const void *head_weight, double *logq, double *logm) {
+  if (T_max < 1 || T_max > ORACLE_MAX_TREE || vocab < 1 || hidden < 1) return 1;
+  for (int32_t b = 0; b < B; ++b) {
+    if (n_nodes[b] > T_max) return 1;
+    int rc = check_tree(n_nodes[b], parent + (int64_t)b * T_max);
+    if (rc) return rc;
+    for (int32_t c = 1; c < n_nodes[b]; ++c) {
+      int32_t t = token[(int64_t)b * T_max + c];
+      if (t < 0 || t >= vocab) return 6;
+    }
+  }
+  for (int64_t x = 0; x < (int64_t)B * T_max; ++x) logq[x] = logm[x] = 0.0;
+  int failed = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int64_t bp = 0; bp < (int64_t)B * T_max; ++bp) {
+    int32_t b = (int32_t)(bp / T_max), p = (int32_t)(bp % T_max);
+    int32_t T = n_nodes[b];
+    if (p >= T) continue;
+    const int32_t *par = parent + (int64_t)b * T_max;
+    int has_child = 0;
+    for (int32_t c = p + 1; c < T; ++c) has_child |= (par[c] == p);
+    if (!has_child) continue;
+    double *z = (double *)malloc(sizeof(double) * (size_t)vocab);
+    if (!z) {
+      failed = 1;
+      continue;
+    }
+    double zmax = -INFINITY;
+    for (int32_t v = 0; v < vocab; ++v) {
+      double acc = 0.0;
+      for (int32_t x = 0; x < hidden; ++x)
+        acc += load_value(hidden_states, dtype, bp * hidden + x) *
+               load_value(head_weight, dtype, (int64_t)v * hidden + x);
+      z[v] = acc;
+      if (acc > zmax) zmax = acc;
+    }
+    double sum = 0.0;
+    for (int32_t v = 0; v < vocab; ++v) sum += exp(z[v] - zmax);
+    double lse = zmax + log(sum);
+    for (int32_t c = p + 1; c < T; ++c)
+      if (par[c] == p) logq[(int64_t)b * T_max + c] = z[token[(int64_t)b * T_max + c]] - lse;
+    free(z);
+  }
+  if (failed) return 5;
+  for (int32_t b = 0; b < B; ++b)
+    for (int32_t c = 1; c < n_nodes[b]; ++c) {
+      int64_t o = (int64_t)b * T_max;
+      logm[o + c] = logm[o + parent[o + c]] + logq[o + c];
+    }
+  return 0;
+}
+
+/*
  * Branch elimination, compaction and mask subsampling (Section 4.1, third
  * step of "Pruning Process" and "Implementation Optimization").  A token
  * fails when its rank is not below k; every candidate sequence that contains a
