@@ -192,6 +192,38 @@ PROPD_API propd_status propd_accept_path(const propd_tree *tree, propd_dtype dt,
                                size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Early pruning by the probability-based criterion (Section 4.1, "Pruning Criterion", the
+ * second of the two criteria; the paper sets it aside because its implementation moved the
+ * probabilities to the host - here everything stays on the device).  The early head's scores
+ * of a node become probabilities, q_c = softmax(z_p)[tok_c] for a child c of p, and the
+ * candidate sequence that ends in node i gets the marginal probability of its tokens,
+ * m_i = product of q over the root path of i (root excluded, m_root = 1).  Then either
+ *   PROPD_PROB_THRESHOLD  node i goes when m_i < threshold (0 <= threshold <= 1), or
+ *   PROPD_PROB_RANK       node i goes when keep_count or more nodes of its tree have a larger
+ *                         marginal (equal marginals: the lower node index counts as larger),
+ *                         i.e. the keep_count most probable sequences stay (keep_count >= 1).
+ * Marginals never grow along a path, so both rules remove whole branches; the root always
+ * stays; a token id outside [0,vocab) has probability 0 and always goes.  What follows the
+ * decision - compaction, mask subsampling, payload rows, every output - is exactly as in
+ * propd_early_prune, with the same arguments, layouts and workspace size.
+ *
+ *   log_marginal  [B,T_max] fp32 or NULL: log m_i of every node of the INPUT tree (0 for the
+ *                 root and for padding), fully written
+ * Scores are accumulated in fp32 and the marginals are summed in fp32 as logarithms: a
+ * decision can differ from an exact evaluation where log m_i is within about 1e-3 of the
+ * boundary.
+ */
+typedef enum { PROPD_PROB_THRESHOLD = 0, PROPD_PROB_RANK = 1 } propd_prob_mode;
+PROPD_API propd_status propd_early_prune_prob(const propd_tree *tree, propd_dtype dt, int32_t hidden, int32_t vocab,
+                               propd_prob_mode mode, float threshold, int32_t keep_count,
+                               const void *hidden_states, const void *head_weight,
+                               uint64_t *keep_bits, int32_t *new_index, int32_t *orig_index,
+                               int32_t *n_kept, int32_t *cu_nodes, const propd_tree_out *tree_out,
+                               float *log_marginal, int32_t n_payloads,
+                               const propd_payload *payloads, void *workspace,
+                               size_t workspace_bytes, void *hip_stream);
+
+/*
  * Commit of the accepted path: what a decoding loop does between acceptance and the next
  * step (Section 2, "Verification": the longest verified sequence is kept; Section 5.1:
  * greedy decoding).  With a = accept_len[b] and L = seq_lens[b]:

@@ -24,7 +24,7 @@ MAX_TREE = 128
 MAX_PAYLOADS = 8
 
 EXPORTS = ("propd_tree_mask", "propd_tree_attention", "propd_early_prune", "propd_accept_path",
-           "propd_commit_path", "propd_workspace_bytes", "propd_status_string",
+           "propd_early_prune_prob", "propd_commit_path", "propd_workspace_bytes", "propd_status_string",
            "propd_controller_bytes", "propd_controller_init", "propd_controller_observe_time",
            "propd_controller_observe_hit", "propd_controller_fit", "propd_controller_build_tree",
            "propd_controller_best_size")
@@ -70,6 +70,11 @@ def load_library() -> ctypes.CDLL:
     lib.propd_early_prune.argtypes = [ctypes.POINTER(_Tree), ctypes.c_int, i32, i32, i32, vp, vp,
                                       vp, vp, vp, vp, vp, ctypes.POINTER(_TreeOut), vp, i32,
                                       ctypes.POINTER(_Payload), vp, sz, vp]
+    lib.propd_early_prune_prob.restype = ctypes.c_int
+    lib.propd_early_prune_prob.argtypes = [ctypes.POINTER(_Tree), ctypes.c_int, i32, i32, ctypes.c_int,
+                                           ctypes.c_float, i32, vp, vp, vp, vp, vp, vp, vp,
+                                           ctypes.POINTER(_TreeOut), vp, i32,
+                                           ctypes.POINTER(_Payload), vp, sz, vp]
     lib.propd_accept_path.restype = ctypes.c_int
     lib.propd_accept_path.argtypes = [ctypes.POINTER(_Tree), ctypes.c_int, i32, vp, vp, vp, i32, vp,
                                       vp, sz, vp]
@@ -234,6 +239,7 @@ class PruneResult:
     tree: Tree                # compacted tree
     rank: Optional[torch.Tensor]
     payloads: list
+    log_marginal: Optional[torch.Tensor] = None   # float32 [B,T_max], probability criterion only
 
 
 def propd_early_prune(tree: Tree, hidden_states: torch.Tensor, head_weight: torch.Tensor,
@@ -242,6 +248,28 @@ def propd_early_prune(tree: Tree, hidden_states: torch.Tensor, head_weight: torc
                       want_rank: bool = False,
                       workspace: Optional[torch.Tensor] = None) -> PruneResult:
     """``payloads`` are tensors shaped [B,T_max,C] or [B,outer,T_max,C] to narrow to survivors."""
+    return _early_prune(("topk", top_k), tree, hidden_states, head_weight, payloads, payload_out,
+                        want_rank, workspace)
+
+
+def propd_early_prune_prob(tree: Tree, hidden_states: torch.Tensor, head_weight: torch.Tensor,
+                           threshold: Optional[float] = None, keep_count: Optional[int] = None,
+                           payloads: Sequence[torch.Tensor] = (),
+                           payload_out: Optional[Sequence[torch.Tensor]] = None,
+                           want_log_marginal: bool = False,
+                           workspace: Optional[torch.Tensor] = None) -> PruneResult:
+    """Probability-based criterion: give exactly one of ``threshold`` (a probability) and
+    ``keep_count`` (sequences kept per tree)."""
+    if (threshold is None) == (keep_count is None):
+        raise ValueError("give exactly one of threshold and keep_count")
+    crit = ("threshold", float(threshold)) if keep_count is None else ("rank", int(keep_count))
+    return _early_prune(crit, tree, hidden_states, head_weight, payloads, payload_out,
+                        want_log_marginal, workspace)
+
+
+def _early_prune(crit, tree, hidden_states, head_weight, payloads, payload_out, want_extra,
+                 workspace) -> PruneResult:
+    want_rank = want_extra and crit[0] == "topk"
     dt = _dt(hidden_states)
     B, T_max, hidden = hidden_states.shape
     vocab = head_weight.shape[0]
@@ -280,11 +308,22 @@ def propd_early_prune(tree: Tree, hidden_states: torch.Tensor, head_weight: torc
     ws = _workspace(workspace_bytes(WS_EARLY_PRUNE, B, T_max, hidden=hidden, vocab=vocab), dev,
                     workspace)
     c_tree = tree._c()
-    _check(load_library().propd_early_prune(
-        ctypes.byref(c_tree), dt, hidden, vocab, top_k, _ptr(hidden_states), _ptr(head_weight),
-        _ptr(res.keep_bits), _ptr(res.new_index), _ptr(res.orig_index), _ptr(res.n_kept),
-        _ptr(res.cu_nodes), ctypes.byref(t_out), _ptr(res.rank), len(payloads), descs, _ptr(ws),
-        ws.numel() * ws.element_size(), _stream()), "propd_early_prune")
+    if crit[0] == "topk":
+        _check(load_library().propd_early_prune(
+            ctypes.byref(c_tree), dt, hidden, vocab, crit[1], _ptr(hidden_states), _ptr(head_weight),
+            _ptr(res.keep_bits), _ptr(res.new_index), _ptr(res.orig_index), _ptr(res.n_kept),
+            _ptr(res.cu_nodes), ctypes.byref(t_out), _ptr(res.rank), len(payloads), descs, _ptr(ws),
+            ws.numel() * ws.element_size(), _stream()), "propd_early_prune")
+    else:
+        if want_extra:
+            res.log_marginal = torch.empty((B, T_max), dtype=torch.float32, device=dev)
+        mode = 0 if crit[0] == "threshold" else 1
+        _check(load_library().propd_early_prune_prob(
+            ctypes.byref(c_tree), dt, hidden, vocab, mode, crit[1] if mode == 0 else 0.0,
+            crit[1] if mode == 1 else 0, _ptr(hidden_states), _ptr(head_weight),
+            _ptr(res.keep_bits), _ptr(res.new_index), _ptr(res.orig_index), _ptr(res.n_kept),
+            _ptr(res.cu_nodes), ctypes.byref(t_out), _ptr(res.log_marginal), len(payloads), descs,
+            _ptr(ws), ws.numel() * ws.element_size(), _stream()), "propd_early_prune_prob")
     return res
 
 

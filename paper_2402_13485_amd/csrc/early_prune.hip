@@ -11,6 +11,9 @@
 //   early_head_f32_kernel plain fp32 variant
 //   rank_count_kernel     per parent row: rank of every child's token by
 //                         counting scores that beat it (the top-k membership test)
+//   child_logprob_kernel  probability criterion: log-sum-exp of every parent row and the
+//                         log-probability of every child's token
+//   prob_decide_kernel    probability criterion: path marginals, threshold or rank test
 //   prune_compact_kernel  per sequence: fail bits by ballot, branch elimination
 //                         by testing the cached ancestor bitset against the fail
 //                         bits, order-preserving compaction by prefix popcount,
@@ -30,6 +33,7 @@ struct PruneScratch {
   int32_t *local_list;  // [B*T_max]  per sequence: nodes with children, ascending
   int32_t *row_src;     // [B*T_max]  global row -> b*T_max + node
   int32_t *row_base;    // [B+1]      exclusive prefix of n_par; [B] = total rows
+  float *logq;          // [B*T_max]  probability criterion: log q of every node's token
   float *scores;        // [row_cap * score_pitch]
   size_t row_cap, score_pitch, total_bytes;
 };
@@ -49,6 +53,7 @@ static PruneScratch carve_scratch(void *base, int B, int T_max, int vocab) {
   s.local_list = reinterpret_cast<int32_t *>(take(nt * 4));
   s.row_src = reinterpret_cast<int32_t *>(take(nt * 4));
   s.row_base = reinterpret_cast<int32_t *>(take((size_t)(B + 1) * 4));
+  s.logq = reinterpret_cast<float *>(take(nt * 4));
   s.row_cap = (size_t)B * (T_max > 1 ? T_max - 1 : 1);  // a node with children is not a leaf
   s.score_pitch = align_up((size_t)vocab, 4);
   s.scores = reinterpret_cast<float *>(take(s.row_cap * s.score_pitch * 4));
@@ -437,11 +442,82 @@ __global__ __launch_bounds__(256) void early_head_f32_kernel(
 // ------------------------------------------------------------------------------------
 constexpr int kRankThreads = 256;
 constexpr int kRankChunk = 8;     // children compared per pass over the scores
-constexpr int kRankSplit = 8;     // workgroups sharing one parent row (column slices)
+constexpr int kRankSplit = 4;     // workgroups sharing one parent row (column slices)
+
+// One pass over a slice of a score row for NC children at once: counts, per child, the scores
+// that beat its token's (a higher score, or the same score at a lower id), adds the counts of
+// the workgroup up in LDS and then onto the children's ranks.
+template <int NC>
+__device__ __forceinline__ void rank_pass(int b, int T_max, int vocab, int c0, int nchild, int part,
+                                          int c_lo, int c_hi, int nvec, const float *__restrict__ z,
+                                          const int32_t *__restrict__ token, const int *s_child,
+                                          int *s_count, int32_t *__restrict__ rank) {
+  const int tid = threadIdx.x;
+  float thr[NC];
+  int tok[NC], cnt[NC];
+#pragma unroll
+  for (int e = 0; e < NC; ++e) {
+    thr[e] = INFINITY;  // unused slot: nothing beats +inf, nothing ties below id -1
+    tok[e] = -1;
+    cnt[e] = 0;
+    if (c0 + e < nchild) {
+      const int t = token[(size_t)b * T_max + s_child[c0 + e]];
+      if (t >= 0 && t < vocab) {
+        thr[e] = z[t];
+        tok[e] = t;
+      }
+    }
+  }
+  if (tid < NC) s_count[tid] = 0;
+  __syncthreads();
+  for (int c = c_lo + tid; c < c_hi; c += kRankThreads) {
+    const f32x4 u = *reinterpret_cast<const f32x4 *>(z + 4 * c);
+    const int v = 4 * c;
+#pragma unroll
+    for (int e = 0; e < NC; ++e) {
+      cnt[e] += (u.x > thr[e]) || (u.x == thr[e] && v < tok[e]);
+      cnt[e] += (u.y > thr[e]) || (u.y == thr[e] && v + 1 < tok[e]);
+      cnt[e] += (u.z > thr[e]) || (u.z == thr[e] && v + 2 < tok[e]);
+      cnt[e] += (u.w > thr[e]) || (u.w == thr[e] && v + 3 < tok[e]);
+    }
+  }
+  if (part == kRankSplit - 1)
+    for (int v = 4 * nvec + tid; v < vocab; v += kRankThreads) {
+      const float x = z[v];
+#pragma unroll
+      for (int e = 0; e < NC; ++e) cnt[e] += (x > thr[e]) || (x == thr[e] && v < tok[e]);
+    }
+#pragma unroll
+  for (int e = 0; e < NC; ++e) {
+    const int sum = wave_reduce_sum(cnt[e]);
+    if ((tid & 63) == 0 && sum) atomicAdd(&s_count[e], sum);
+  }
+  __syncthreads();
+  if (tid < NC && c0 + tid < nchild) {
+    int mine = 0;
+    bool valid_tok = false;
+#pragma unroll
+    for (int e = 0; e < NC; ++e)
+      if (e == tid) {
+        mine = s_count[e];
+        valid_tok = tok[e] >= 0;
+      }
+    int32_t *dst = &rank[(size_t)b * T_max + s_child[c0 + tid]];
+    // a token id outside the vocabulary can be in no top-k list
+    if (!valid_tok) {
+      if (part == 0) atomicAdd(dst, vocab);
+    } else if (mine) {
+      atomicAdd(dst, mine);
+    }
+  }
+  __syncthreads();
+}
 
 // One parent row is shared by kRankSplit workgroups, each counting over its own slice of
 // the vocabulary and adding its counts to the children's ranks with integer atomics (the
 // sum does not depend on the order).  ranks of children were zeroed by parent_rows_kernel.
+// Children are taken up to kRankChunk at a time, in a pass specialised for 1, 2, 4 or 8 of
+// them: most nodes have one or two children and the compare work goes with that number.
 __global__ __launch_bounds__(kRankThreads) void rank_count_kernel(
     int B, int T_max, int vocab, const int32_t *__restrict__ n_nodes,
     const int32_t *__restrict__ parent, const int32_t *__restrict__ token,
@@ -470,66 +546,123 @@ __global__ __launch_bounds__(kRankThreads) void rank_count_kernel(
   const int c_lo = part * per, c_hi = (c_lo + per < nvec) ? c_lo + per : nvec;
 
   for (int c0 = 0; c0 < nchild; c0 += kRankChunk) {
-    float thr[kRankChunk];
-    int tok[kRankChunk];
-    int cnt[kRankChunk];
+    const int here = nchild - c0;
+    if (here <= 1)
+      rank_pass<1>(b, T_max, vocab, c0, nchild, part, c_lo, c_hi, nvec, z, token, s_child, s_count, rank);
+    else if (here <= 2)
+      rank_pass<2>(b, T_max, vocab, c0, nchild, part, c_lo, c_hi, nvec, z, token, s_child, s_count, rank);
+    else if (here <= 4)
+      rank_pass<4>(b, T_max, vocab, c0, nchild, part, c_lo, c_hi, nvec, z, token, s_child, s_count, rank);
+    else
+      rank_pass<kRankChunk>(b, T_max, vocab, c0, nchild, part, c_lo, c_hi, nvec, z, token, s_child, s_count, rank);
+  }
+}
+
+// ------------------------------------------------------------------------------------
+// probability-based selection (Section 4.1, "Pruning Criterion", second criterion)
+// ------------------------------------------------------------------------------------
+constexpr int kLseThreads = 256;
+
+// (max, sum of exp(x - max)) of two parts of a row, merged
+__device__ __forceinline__ void lse_merge(float &m, float &s, float m2, float s2) {
+  const float mm = m > m2 ? m : m2;
+  s = (m == -INFINITY ? 0.f : s * expf(m - mm)) + (m2 == -INFINITY ? 0.f : s2 * expf(m2 - mm));
+  m = mm;
+}
+
+// One workgroup per parent row: one pass over the row's scores for log sum_v exp(z[v]), then
+// logq = z[token] - that for every child of the row's node.  A token id outside the
+// vocabulary has probability 0 (logq = -inf).
+__global__ __launch_bounds__(kLseThreads) void child_logprob_kernel(
+    int B, int T_max, int vocab, const int32_t *__restrict__ n_nodes,
+    const int32_t *__restrict__ parent, const int32_t *__restrict__ token,
+    const int32_t *__restrict__ row_src, const int32_t *__restrict__ row_base,
+    const float *__restrict__ scores, size_t score_pitch, float *__restrict__ logq) {
+  const int m = blockIdx.x;
+  if (m >= row_base[B]) return;
+  const int node = row_src[m];
+  const int b = node / T_max, p = node - b * T_max;
+  int T = n_nodes[b];
+  T = T < 1 ? 1 : (T > T_max ? T_max : T);
+  const int tid = threadIdx.x;
+  const float *z = scores + (size_t)m * score_pitch;
+  float mx = -INFINITY, sum = 0.f;
+  const int nvec = vocab >> 2;
+  for (int c = tid; c < nvec; c += kLseThreads) {
+    const f32x4 u = *reinterpret_cast<const f32x4 *>(z + 4 * c);
+    const float m4 = fmaxf(fmaxf(u.x, u.y), fmaxf(u.z, u.w));
+    const float s4 = expf(u.x - m4) + expf(u.y - m4) + expf(u.z - m4) + expf(u.w - m4);
+    lse_merge(mx, sum, m4, s4);
+  }
+  for (int v = 4 * nvec + tid; v < vocab; v += kLseThreads) lse_merge(mx, sum, z[v], 1.f);
 #pragma unroll
-    for (int e = 0; e < kRankChunk; ++e) {
-      thr[e] = INFINITY;  // unused slot: nothing beats +inf, nothing ties below id -1
-      tok[e] = -1;
-      cnt[e] = 0;
-      if (c0 + e < nchild) {
-        const int t = token[(size_t)b * T_max + s_child[c0 + e]];
-        if (t >= 0 && t < vocab) {
-          thr[e] = z[t];
-          tok[e] = t;
-        }
-      }
+  for (int o = 32; o > 0; o >>= 1) {
+    const float m2 = __shfl_xor(mx, o, kWave), s2 = __shfl_xor(sum, o, kWave);
+    lse_merge(mx, sum, m2, s2);
+  }
+  __shared__ float s_m[kLseThreads / kWave], s_s[kLseThreads / kWave];
+  if ((tid & 63) == 0) {
+    s_m[tid >> 6] = mx;
+    s_s[tid >> 6] = sum;
+  }
+  __syncthreads();
+  mx = s_m[0];
+  sum = s_s[0];
+#pragma unroll
+  for (int w = 1; w < kLseThreads / kWave; ++w) lse_merge(mx, sum, s_m[w], s_s[w]);
+  const float lse = mx + logf(sum);
+  if (tid > p && tid < T && parent[(size_t)b * T_max + tid] == p) {
+    const int t = token[(size_t)b * T_max + tid];
+    logq[(size_t)b * T_max + tid] = (t >= 0 && t < vocab) ? z[t] - lse : -INFINITY;
+  }
+}
+
+// One workgroup per sequence, one lane per node: the log marginal of a node's sequence is the
+// sum of logq over its root path (the cached ancestor set, root excluded, in root-to-node
+// order); then the test.  mode 0: pruned when the marginal is below the threshold; mode 1:
+// pruned when `keep_count` or more sequences of the tree are more probable (equal marginals:
+// the lower node index counts as more probable).  A marginal of zero probability is always
+// pruned.  The result is written as a 0/1 "rank" for prune_compact_kernel with k = 1.
+__global__ __launch_bounds__(PROPD_MAX_TREE) void prob_decide_kernel(
+    int T_max, int mode, float log_threshold, int keep_count, const int32_t *__restrict__ n_nodes,
+    const uint64_t *__restrict__ anc, const float *__restrict__ logq, int32_t *__restrict__ rank,
+    float *__restrict__ log_marginal) {
+  const int b = blockIdx.x, i = threadIdx.x;
+  int T = n_nodes[b];
+  T = T < 1 ? 1 : (T > T_max ? T_max : T);
+  const size_t base = (size_t)b * T_max;
+  const bool valid = i < T;
+  __shared__ float s_q[PROPD_MAX_TREE], s_lm[PROPD_MAX_TREE];
+  s_q[i] = (valid && i > 0) ? logq[base + i] : 0.f;
+  __syncthreads();
+  float lm = 0.f;
+  if (valid && i > 0) {
+    uint64_t lo = anc[(base + i) * 2] & ~1ull, hi = anc[(base + i) * 2 + 1];
+    while (lo) {
+      lm += s_q[__ffsll((long long)lo) - 1];
+      lo &= lo - 1;
     }
-    if (tid < kRankChunk) s_count[tid] = 0;
-    __syncthreads();
-    for (int c = c_lo + tid; c < c_hi; c += kRankThreads) {
-      const f32x4 u = *reinterpret_cast<const f32x4 *>(z + 4 * c);
-      const int v = 4 * c;
-#pragma unroll
-      for (int e = 0; e < kRankChunk; ++e) {
-        cnt[e] += (u.x > thr[e]) || (u.x == thr[e] && v < tok[e]);
-        cnt[e] += (u.y > thr[e]) || (u.y == thr[e] && v + 1 < tok[e]);
-        cnt[e] += (u.z > thr[e]) || (u.z == thr[e] && v + 2 < tok[e]);
-        cnt[e] += (u.w > thr[e]) || (u.w == thr[e] && v + 3 < tok[e]);
-      }
+    while (hi) {
+      lm += s_q[64 + __ffsll((long long)hi) - 1];
+      hi &= hi - 1;
     }
-    if (part == kRankSplit - 1)
-      for (int v = 4 * nvec + tid; v < vocab; v += kRankThreads) {
-        const float x = z[v];
-#pragma unroll
-        for (int e = 0; e < kRankChunk; ++e)
-          cnt[e] += (x > thr[e]) || (x == thr[e] && v < tok[e]);
-      }
-#pragma unroll
-    for (int e = 0; e < kRankChunk; ++e) {
-      const int sum = wave_reduce_sum(cnt[e]);
-      if ((tid & 63) == 0 && sum) atomicAdd(&s_count[e], sum);
+  }
+  s_lm[i] = valid ? lm : -INFINITY;
+  __syncthreads();
+  bool fail = false;
+  if (valid && i > 0) {
+    if (mode == 0) {
+      fail = !(lm >= log_threshold);
+    } else {
+      int ahead = 0;
+      for (int j = 0; j < T; ++j) ahead += (s_lm[j] > lm) || (s_lm[j] == lm && j < i);
+      fail = ahead >= keep_count;
     }
-    __syncthreads();
-    if (tid < kRankChunk && c0 + tid < nchild) {
-      int mine = 0;
-      bool valid_tok = false;
-#pragma unroll
-      for (int e = 0; e < kRankChunk; ++e)
-        if (e == tid) {
-          mine = s_count[e];
-          valid_tok = tok[e] >= 0;
-        }
-      int32_t *dst = &rank[(size_t)b * T_max + s_child[c0 + tid]];
-      // a token id outside the vocabulary can be in no top-k list
-      if (!valid_tok) {
-        if (part == 0) atomicAdd(dst, vocab);
-      } else if (mine) {
-        atomicAdd(dst, mine);
-      }
-    }
-    __syncthreads();
+    fail = fail || !(lm > -INFINITY);
+  }
+  if (i < T_max) {
+    rank[base + i] = valid ? (fail ? 1 : 0) : -1;
+    if (log_marginal) log_marginal[base + i] = valid ? lm : 0.f;
   }
 }
 
@@ -699,13 +832,25 @@ static int prune_compute_units() {
   return cus;
 }
 
-extern "C" propd_status propd_early_prune(
-    const propd_tree *tree, propd_dtype dt, int32_t hidden, int32_t vocab, int32_t top_k,
+namespace {
+// which criterion decides (Section 4.1, "Pruning Criterion")
+struct Criterion {
+  int kind;             // 0 top-k, 1 probability threshold, 2 probability rank
+  int top_k;            // kind 0
+  float log_threshold;  // kind 1
+  int keep_count;       // kind 2
+  float *log_marginal;  // kinds 1, 2: optional output
+};
+}  // namespace
+
+static propd_status prune_impl(
+    const Criterion &crit, const propd_tree *tree, propd_dtype dt, int32_t hidden, int32_t vocab,
     const void *hidden_states, const void *head_weight, uint64_t *keep_bits, int32_t *new_index,
     int32_t *orig_index, int32_t *n_kept, int32_t *cu_nodes, const propd_tree_out *tree_out,
     int32_t *rank_out, int32_t n_payloads, const propd_payload *payloads, void *workspace,
     size_t workspace_bytes, void *hip_stream) {
   using namespace propd;
+  const int top_k = crit.kind == 0 ? crit.top_k : 1;  // the 0/1 flags of the other kinds pass below 1
   if (!tree || tree->B < 1 || tree->T_max < 1 || tree->T_max > PROPD_MAX_TREE || hidden < 1 ||
       vocab < 1 || top_k < 1)
     return PROPD_ERR_INVALID_ARG;
@@ -755,7 +900,7 @@ extern "C" propd_status propd_early_prune(
   PruneScratch ws = carve_scratch(workspace, B, T_max, vocab);
   hipStream_t st = as_stream(hip_stream);
 
-  if (top_k >= vocab) {
+  if (crit.kind == 0 && top_k >= vocab) {
     // every id is inside the list: nothing can fail, no scores are needed
     const int n = B * T_max;
     hipLaunchKernelGGL(fill_rank_kernel, dim3((n + 255) / 256), dim3(256), 0, st, n, T_max,
@@ -791,9 +936,18 @@ extern "C" propd_status propd_early_prune(
                          reinterpret_cast<const float *>(head_weight), ws.row_src, ws.row_base,
                          ws.scores, ws.score_pitch);
     }
-    hipLaunchKernelGGL(rank_count_kernel, dim3((unsigned)(ws.row_cap * kRankSplit)), dim3(kRankThreads), 0, st, B,
-                       T_max, vocab, tree->n_nodes, tree->parent, tree->token, ws.row_src,
-                       ws.row_base, ws.scores, ws.score_pitch, ws.rank);
+    if (crit.kind == 0) {
+      hipLaunchKernelGGL(rank_count_kernel, dim3((unsigned)(ws.row_cap * kRankSplit)), dim3(kRankThreads), 0, st, B,
+                         T_max, vocab, tree->n_nodes, tree->parent, tree->token, ws.row_src,
+                         ws.row_base, ws.scores, ws.score_pitch, ws.rank);
+    } else {
+      hipLaunchKernelGGL(child_logprob_kernel, dim3((unsigned)ws.row_cap), dim3(kLseThreads), 0, st, B,
+                         T_max, vocab, tree->n_nodes, tree->parent, tree->token, ws.row_src,
+                         ws.row_base, ws.scores, ws.score_pitch, ws.logq);
+      hipLaunchKernelGGL(prob_decide_kernel, dim3(B), dim3(PROPD_MAX_TREE), 0, st, T_max,
+                         crit.kind == 1 ? 0 : 1, crit.log_threshold, crit.keep_count, tree->n_nodes,
+                         tree->anc, ws.logq, ws.rank, crit.log_marginal);
+    }
   }
   if (!launch_ok()) return PROPD_ERR_DEVICE;
   hipLaunchKernelGGL(prune_compact_kernel, dim3(B), dim3(PROPD_MAX_TREE), 0, st, T_max, top_k,
@@ -808,4 +962,39 @@ extern "C" propd_status propd_early_prune(
                        orig_index, n_kept);
   }
   return launch_ok() ? PROPD_OK : PROPD_ERR_DEVICE;
+}
+
+extern "C" propd_status propd_early_prune(
+    const propd_tree *tree, propd_dtype dt, int32_t hidden, int32_t vocab, int32_t top_k,
+    const void *hidden_states, const void *head_weight, uint64_t *keep_bits, int32_t *new_index,
+    int32_t *orig_index, int32_t *n_kept, int32_t *cu_nodes, const propd_tree_out *tree_out,
+    int32_t *rank_out, int32_t n_payloads, const propd_payload *payloads, void *workspace,
+    size_t workspace_bytes, void *hip_stream) {
+  if (top_k < 1) return PROPD_ERR_INVALID_ARG;
+  const Criterion crit = {0, top_k, 0.f, 0, nullptr};
+  return prune_impl(crit, tree, dt, hidden, vocab, hidden_states, head_weight, keep_bits, new_index,
+                    orig_index, n_kept, cu_nodes, tree_out, rank_out, n_payloads, payloads,
+                    workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" propd_status propd_early_prune_prob(
+    const propd_tree *tree, propd_dtype dt, int32_t hidden, int32_t vocab, propd_prob_mode mode,
+    float threshold, int32_t keep_count, const void *hidden_states, const void *head_weight,
+    uint64_t *keep_bits, int32_t *new_index, int32_t *orig_index, int32_t *n_kept,
+    int32_t *cu_nodes, const propd_tree_out *tree_out, float *log_marginal, int32_t n_payloads,
+    const propd_payload *payloads, void *workspace, size_t workspace_bytes, void *hip_stream) {
+  Criterion crit = {1, 1, 0.f, 0, log_marginal};
+  if (mode == PROPD_PROB_THRESHOLD) {
+    if (!(threshold >= 0.f) || threshold > 1.f) return PROPD_ERR_INVALID_ARG;
+    crit.log_threshold = threshold > 0.f ? logf(threshold) : -INFINITY;
+  } else if (mode == PROPD_PROB_RANK) {
+    if (keep_count < 1) return PROPD_ERR_INVALID_ARG;
+    crit.kind = 2;
+    crit.keep_count = keep_count;
+  } else {
+    return PROPD_ERR_INVALID_ARG;
+  }
+  return prune_impl(crit, tree, dt, hidden, vocab, hidden_states, head_weight, keep_bits, new_index,
+                    orig_index, n_kept, cu_nodes, tree_out, nullptr, n_payloads, payloads,
+                    workspace, workspace_bytes, hip_stream);
 }

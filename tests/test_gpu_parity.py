@@ -411,6 +411,10 @@ def test_workspace_bounds_respected(pb, oracle):
     pb.propd_early_prune(tree, to_dev(xp["hidden_states"]), to_dev(xp["head_weight"]), 5,
                          workspace=ws)
     assert intact(ws, n)
+    ws, n = guarded(pb.workspace_bytes(pb.WS_EARLY_PRUNE, 3, 64, hidden=256, vocab=1000))
+    pb.propd_early_prune_prob(tree, to_dev(xp["hidden_states"]), to_dev(xp["head_weight"]),
+                              keep_count=9, want_log_marginal=True, workspace=ws)
+    assert intact(ws, n)
     acc = synth.make_accept_inputs(w, xp["n_nodes"], xp["parent"], xp["token"])
     ws, n = guarded(pb.workspace_bytes(pb.WS_ACCEPT_PATH, 3, 64, vocab=1000))
     pb.propd_accept_path(tree, to_dev(acc["logits"]), workspace=ws)
@@ -489,3 +493,116 @@ def test_commit_path_bad_indices_write_nothing(pb):
     assert (got[2, :, 2] == kt[2, :, 2]).all() and (got[2, :, 3] == kt[2, :, 3]).all()
     assert (got[2, :, 4:] == kc[2, :, 4:]).all()
     assert to_host(out).tolist() == [[-1, 2, 9, -1], [-1, 9, -1, -1], [-1, 18, 19, 9]]
+
+
+# ------------------------------------------------------------------ probability-based pruning
+
+
+def prob_reference(oracle, x, threshold=None, keep_count=None):
+    """Oracle decisions + compaction, and the distance of every decision from its boundary."""
+    _, logm = oracle.early_head_logprob(x["n_nodes"], x["parent"], x["token"], x["hidden_states"],
+                                        x["head_weight"])
+    fail = oracle.prob_fail_flags(x["n_nodes"], logm, threshold=threshold, keep_count=keep_count)
+    ref = oracle.prune_compact(x["n_nodes"], x["parent"], x["token"], fail, 1)
+    return logm, fail, ref
+
+
+def threshold_in_a_gap(logm, n_nodes, tau, quantile=0.5):
+    """A probability threshold whose logarithm sits in the middle of a gap of at least 2*tau
+    between the marginals of the batch, near the given quantile."""
+    vals = np.sort(np.concatenate([logm[b, 1:int(n)] for b, n in enumerate(n_nodes)]))
+    gaps = np.diff(vals)
+    order = np.argsort(np.abs(np.arange(len(gaps)) - quantile * len(gaps)))
+    j = next(int(j) for j in order if gaps[j] >= 2 * tau)
+    return float(np.exp(0.5 * (vals[j] + vals[j + 1])))
+
+
+def check_prob(pb, oracle, x, res, ref, logm, payload_arrays=(), sentinels=()):
+    lm = to_host(res.log_marginal).astype(np.float64)
+    for b, n in enumerate(x["n_nodes"]):
+        assert np.abs(lm[b, :int(n)] - logm[b, :int(n)]).max() < 2e-4 * max(1.0, np.abs(logm[b, :int(n)]).max())
+        assert (lm[b, int(n):] == 0).all()
+    assert (u64(res.keep_bits) == ref["keep_bits"]).all()
+    for name in ("new_index", "orig_index", "n_kept", "cu_nodes"):
+        assert (to_host(getattr(res, name)) == ref[name]).all(), name
+    assert (to_host(res.tree.n_nodes) == ref["n_kept"]).all()
+    for name in ("parent", "token", "depth"):
+        assert (to_host(getattr(res.tree, name)) == ref[name]).all(), name
+    assert (u64(res.tree.anc) == ref["anc"]).all()
+    for arr, sent, got in zip(payload_arrays, sentinels, res.payloads):
+        want = oracle.gather_rows(arr, ref["orig_index"], ref["n_kept"], fill_from=sent)
+        assert (to_host(got) == want).all()
+
+
+def run_prob(pb, x, payload_arrays=(), **crit):
+    tree = dev_tree(pb, x["n_nodes"], x["parent"], x["token"])
+    payloads = [to_dev(a) for a in payload_arrays]
+    sentinels = [sentinel_like(a) for a in payload_arrays]
+    res = pb.propd_early_prune_prob(tree, to_dev(x["hidden_states"]), to_dev(x["head_weight"]),
+                                    payloads=payloads, payload_out=[to_dev(s) for s in sentinels],
+                                    want_log_marginal=True, **crit)
+    torch.cuda.synchronize()
+    return res, sentinels
+
+
+@pytest.mark.parametrize("dtype,B,T_max,Hd,V", [("bf16", 3, 64, 256, 1003), ("bf16", 2, 128, 512, 4096),
+                                                ("f32", 2, 16, 64, 256)])
+def test_prob_prune_threshold(pb, oracle, dtype, B, T_max, Hd, V):
+    tau = 1e-3
+    depth = {16: 3, 64: 4, 128: 5}[T_max]
+    rng = np.random.default_rng(500 + V)
+    shapes = [synth.rank_product_tree(T_max, depth)] * (B - 1) + \
+        [synth.random_tree(rng, max(2, T_max // 2), max_depth=6)]
+    w = synth.Workload(80 + B, "case", dtype, B, 2, 128, T_max, Hd, V, 8 if V > 300 else 4, tau)
+    x = synth.make_prune_inputs(w, trees=shapes)
+    kt = synth.normal_bf16(rng, (B, 2, T_max, 128))
+    logm, _, _ = prob_reference(oracle, x, threshold=0.5)
+    for quantile in (0.3, 0.7):
+        thr = threshold_in_a_gap(logm, x["n_nodes"], tau, quantile)
+        thr = float(np.float32(thr))                                   # what the call receives
+        _, fail, ref = prob_reference(oracle, x, threshold=thr)
+        valid = np.arange(T_max)[None, :] < x["n_nodes"][:, None]
+        valid[:, 0] = False
+        assert np.abs(logm[valid] - np.log(thr)).min() >= 0.999 * tau     # decisions are well separated
+        res, sents = run_prob(pb, x, [x["hidden_states"], kt], threshold=thr)
+        check_prob(pb, oracle, x, res, ref, logm, [x["hidden_states"], kt], sents)
+        assert 1 < ref["n_kept"].sum() < x["n_nodes"].sum()
+    # the ends of the range: 0 keeps every sequence, 1 only the roots
+    res, _ = run_prob(pb, x, threshold=0.0)
+    assert (to_host(res.n_kept) == x["n_nodes"]).all()
+    res, _ = run_prob(pb, x, threshold=1.0)
+    assert (to_host(res.n_kept) == 1).all()
+
+
+@pytest.mark.parametrize("B,T_max,Hd,V", [(3, 64, 256, 1003), (2, 128, 512, 4096)])
+def test_prob_prune_rank(pb, oracle, B, T_max, Hd, V):
+    tau = 1e-3
+    depth = {64: 4, 128: 5}[T_max]
+    w = synth.Workload(90 + B, "case", "bf16", B, 2, 128, T_max, Hd, V, 8, tau)
+    x = synth.make_prune_inputs(w, trees=[synth.rank_product_tree(T_max, depth)] * B)
+    logm, _, _ = prob_reference(oracle, x, keep_count=1)
+    srt = -np.sort(-logm[:, :T_max], axis=1)                          # per tree, descending
+    gap = srt[:, :-1] - srt[:, 1:]                                    # gap[b, R-1]: between the R-th and the next
+    candidates = [R for R in range(2, T_max) if gap[:, R - 1].min() >= 2 * tau]
+    assert len(candidates) >= 3
+    for R in (candidates[0], candidates[len(candidates) // 2], candidates[-1]):
+        _, fail, ref = prob_reference(oracle, x, keep_count=R)
+        assert (ref["n_kept"] == R).all()
+        res, _ = run_prob(pb, x, keep_count=R)
+        check_prob(pb, oracle, x, res, ref, logm)
+    res, _ = run_prob(pb, x, keep_count=1)
+    assert (to_host(res.n_kept) == 1).all()
+    res, _ = run_prob(pb, x, keep_count=T_max + 5)
+    assert (to_host(res.n_kept) == T_max).all()
+
+
+def test_prob_prune_token_outside_vocabulary_goes(pb):
+    w = synth.Workload(95, "case", "bf16", 2, 1, 128, 16, 64, 130, 3, 1e-3)
+    x = synth.make_prune_inputs(w, trees=[synth.chain_tree(6), synth.star_tree(5)])
+    x["token"][0, 3] = 130            # one past the vocabulary: node 3 and the chain below it go
+    x["token"][1, 2] = -7
+    res, _ = run_prob(pb, x, threshold=0.0)
+    assert to_host(res.n_kept).tolist() == [3, 4]
+    assert to_host(res.orig_index)[1, :4].tolist() == [0, 1, 3, 4]
+    lm = to_host(res.log_marginal)
+    assert np.isneginf(lm[0, 3:6]).all() and np.isneginf(lm[1, 2]) and np.isfinite(lm[1, [1, 3, 4]]).all()
