@@ -142,6 +142,11 @@ def main() -> int:
                     help="instead of the benchmark line: time the step at tree sizes 16..128 of "
                          "this workload's shape, feed the times to the library's tree-size "
                          "controller and print its estimates and its choice")
+    ap.add_argument("--layers", type=int, default=0,
+                    help="instead of the benchmark line: the attention of a whole model of this "
+                         "many layers per verification step (per-layer synthetic K/V), the "
+                         "pruning pass after --prune-layer of them, at tree sizes 16..128")
+    ap.add_argument("--prune-layer", type=int, default=4)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; nothing here uses a second one "
@@ -164,6 +169,8 @@ def main() -> int:
     w = synth.WORKLOADS[args.workload]
     if args.tree_size_table:
         return tree_size_table(w, args, torch, pb, synth)
+    if args.layers > 0:
+        return multi_layer_table(w, args, torch, pb, synth)
     att, pr, acc, token = build_inputs(w, synth)
     S = resident_step(w, att, pr, acc, token, torch, pb)
     B, H, d, T_max, L_max = S.B, S.H, S.d, S.T_max, S.L_max
@@ -289,6 +296,81 @@ def tree_size_table(w, args, torch, pb, synth):
            "accepted_tokens_per_ms": [float(x) for x in speed], "best_size": best,
            "head_accuracies": "synthetic", "steps": args.steps, "warmup": args.warmup}
     print(json.dumps(out), flush=True)
+    return 0
+
+
+def multi_layer_table(w, args, torch, pb, synth):
+    """The attention and pruning work of one verification step of a whole model (Section 4.1,
+    Figure 5): `prune_layer` layers of tree attention on the full tree, the pruning pass (the
+    hidden state is the only payload: later layers make their own q/k/v from it), the remaining
+    layers on the compacted tree, greedy acceptance.  Every layer has its own synthetic K/V cache
+    and tree q/k/v (drawn on the device); the linear layers of the model are not part of this
+    build, so the figures are the attention side of the step only.  Times it at tree sizes
+    16..128 with and without pruning."""
+    import dataclasses
+    N, n_full = args.layers, min(args.prune_layer, args.layers)
+    B, H, d = w.B, w.H, w.d
+    L = int(synth.workload_seq_lens(w).max())
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(1234)
+    rnd = lambda *shape: torch.randn(shape, device="cuda", generator=gen).to(torch.bfloat16)
+    kc = [rnd(B, H, L, d) for _ in range(N)]
+    vc = [rnd(B, H, L, d) for _ in range(N)]
+    seq = pb.to_device(synth.workload_seq_lens(w))
+    scale = float(d) ** -0.5
+    rows = []
+    for T in [16, 32, 64, 96, 128]:
+        wt = dataclasses.replace(w, T_max=T)
+        trees = synth.workload_trees(wt)
+        pr = synth.make_prune_inputs(wt, trees=trees)
+        n_nodes, parent, _ = synth.pad_trees(trees, T)
+        nn, par = pb.to_device(n_nodes), pb.to_device(parent)
+        depth, anc = pb.propd_tree_mask(nn, par)
+        tree = pb.Tree(n_nodes=nn, parent=par, token=pb.to_device(pr["token"]), depth=depth, anc=anc)
+        q = [rnd(B, H, T, d) for _ in range(N)]
+        kt = [rnd(B, H, T, d) for _ in range(N)]
+        vt = [rnd(B, H, T, d) for _ in range(N)]
+        hid, hw = pb.to_device(pr["hidden_states"]), pb.to_device(pr["head_weight"])
+        hid_out = torch.empty_like(hid)
+        logits = rnd(B, T, w.vocab)
+        out = torch.empty_like(q[0])
+        ws_att = torch.empty(max(256, pb.workspace_bytes(pb.WS_TREE_ATTENTION, B, T, H, d, L)),
+                             dtype=torch.uint8, device="cuda")
+        ws_pr = torch.empty(pb.workspace_bytes(pb.WS_EARLY_PRUNE, B, T, hidden=w.hidden, vocab=w.vocab),
+                            dtype=torch.uint8, device="cuda")
+        ws_acc = torch.empty(pb.workspace_bytes(pb.WS_ACCEPT_PATH, B, T, vocab=w.vocab),
+                             dtype=torch.uint8, device="cuda")
+
+        def step(prune):
+            t = tree
+            for l in range(N):
+                if prune and l == n_full:
+                    t = pb.propd_early_prune(tree, hid, hw, w.top_k, payloads=[hid],
+                                             payload_out=[hid_out], workspace=ws_pr).tree
+                pb.propd_tree_attention(t, q[l], kc[l], vc[l], kt[l], vt[l], seq, scale, out=out,
+                                        workspace=ws_att)
+            return pb.propd_accept_path(t, logits, path_stride=8, workspace=ws_acc), t
+
+        ms = {}
+        for prune in (False, True):
+            for _ in range(2):
+                step(prune)
+            torch.cuda.synchronize()
+            reps = max(3, args.steps // 5)
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                _, t_last = step(prune)
+            torch.cuda.synchronize()
+            ms[prune] = (time.perf_counter() - t0) * 1e3 / reps
+        kept = int(pb.to_host(t_last.n_nodes).sum())
+        rows.append({"tree_size": T, "ms_no_pruning": ms[False], "ms_pruning": ms[True],
+                     "survivors": kept, "tree_tokens": int(n_nodes.sum()),
+                     "tokens_per_s_pruning": float(n_nodes.sum()) / (ms[True] * 1e-3)})
+        log(f"tree size {T}: {ms[False]:.2f} ms without pruning, {ms[True]:.2f} ms with "
+            f"(pruning after layer {n_full}, {kept} of {int(n_nodes.sum())} nodes stay)")
+    print(json.dumps({"mode": "multi_layer_table", "workload": w.name, "layers": N,
+                      "prune_after_layer": n_full, "B": B, "H": H, "L": L, "top_k": w.top_k,
+                      "rows": rows}), flush=True)
     return 0
 
 
