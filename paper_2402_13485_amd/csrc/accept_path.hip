@@ -22,6 +22,14 @@ __device__ __forceinline__ void argmax_take(float x, int idx, float &bv, int &bi
   }
 }
 
+// The same for a lane's own elements, which it visits in rising index order: a strictly larger
+// value replaces the best, so the first of equal values stays.  Branch-free.
+__device__ __forceinline__ void argmax_next(float x, int idx, float &bv, int &bi) {
+  const bool take = x > bv;
+  bv = take ? x : bv;
+  bi = take ? idx : bi;
+}
+
 template <bool kBf16>
 __global__ __launch_bounds__(kArgmaxThreads) void row_argmax_kernel(
     int T_max, int vocab, const int32_t *__restrict__ n_nodes, const void *__restrict__ logits,
@@ -37,38 +45,50 @@ __global__ __launch_bounds__(kArgmaxThreads) void row_argmax_kernel(
     // peel to a 16-byte boundary, then 8 values per load
     int head = (int)(((16 - (reinterpret_cast<uintptr_t>(p) & 15)) & 15) >> 1);
     head = head < vocab ? head : vocab;
-    if (tid < head) argmax_take(bf16_bits_to_f32(p[tid]), tid, bv, bi);
+    if (tid < head) argmax_next(bf16_bits_to_f32(p[tid]), tid, bv, bi);
     const int nvec = (vocab - head) >> 3;
     const u32x4 *pv = reinterpret_cast<const u32x4 *>(p + head);
-    for (int c = tid; c < nvec; c += kArgmaxThreads) {
-      u32x4 u = __builtin_nontemporal_load(pv + c);
-      const int base = head + (c << 3);
-      const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+    // four independent loads in flight per lane before any of them is used
+    constexpr int kInFlight = 4;
+    for (int c0 = tid; c0 < nvec; c0 += kInFlight * kArgmaxThreads) {
+      u32x4 u[kInFlight];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        argmax_take(__uint_as_float(w[e] << 16), base + 2 * e, bv, bi);
-        argmax_take(__uint_as_float(w[e] & 0xffff0000u), base + 2 * e + 1, bv, bi);
+      for (int k = 0; k < kInFlight; ++k) {
+        const int c = c0 + k * kArgmaxThreads;
+        u[k] = __builtin_nontemporal_load(pv + (c < nvec ? c : c0));
+      }
+#pragma unroll
+      for (int k = 0; k < kInFlight; ++k) {
+        const int c = c0 + k * kArgmaxThreads;
+        if (c >= nvec) break;
+        const int base = head + (c << 3);
+        const uint32_t w[4] = {u[k].x, u[k].y, u[k].z, u[k].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          argmax_next(__uint_as_float(w[e] << 16), base + 2 * e, bv, bi);
+          argmax_next(__uint_as_float(w[e] & 0xffff0000u), base + 2 * e + 1, bv, bi);
+        }
       }
     }
     for (int v = head + (nvec << 3) + tid; v < vocab; v += kArgmaxThreads)
-      argmax_take(bf16_bits_to_f32(p[v]), v, bv, bi);
+      argmax_next(bf16_bits_to_f32(p[v]), v, bv, bi);
   } else {
     const float *p = reinterpret_cast<const float *>(logits) + row * (size_t)vocab;
     int head = (int)(((16 - (reinterpret_cast<uintptr_t>(p) & 15)) & 15) >> 2);
     head = head < vocab ? head : vocab;
-    if (tid < head) argmax_take(p[tid], tid, bv, bi);
+    if (tid < head) argmax_next(p[tid], tid, bv, bi);
     const int nvec = (vocab - head) >> 2;
     const f32x4 *pv = reinterpret_cast<const f32x4 *>(p + head);
     for (int c = tid; c < nvec; c += kArgmaxThreads) {
       f32x4 u = __builtin_nontemporal_load(pv + c);
       const int base = head + (c << 2);
-      argmax_take(u.x, base, bv, bi);
-      argmax_take(u.y, base + 1, bv, bi);
-      argmax_take(u.z, base + 2, bv, bi);
-      argmax_take(u.w, base + 3, bv, bi);
+      argmax_next(u.x, base, bv, bi);
+      argmax_next(u.y, base + 1, bv, bi);
+      argmax_next(u.z, base + 2, bv, bi);
+      argmax_next(u.w, base + 3, bv, bi);
     }
     for (int v = head + (nvec << 2) + tid; v < vocab; v += kArgmaxThreads)
-      argmax_take(p[v], v, bv, bi);
+      argmax_next(p[v], v, bv, bi);
   }
   // wave reduction, then across the four waves
 #pragma unroll

@@ -99,25 +99,30 @@ constexpr int kScanThreads = 256;
 // Exclusive prefix sum of in[0..n) into out[0..n], out[n] = total.  One workgroup.
 __device__ void block_exclusive_scan(const int32_t *__restrict__ in, int32_t *__restrict__ out,
                                      int n) {
-  __shared__ int s_part[kScanThreads];
   const int tid = threadIdx.x;
   const int per = (n + kScanThreads - 1) / kScanThreads;
   const int lo = tid * per, hi = (lo + per < n) ? lo + per : n;
   int sum = 0;
   for (int x = lo; x < hi; ++x) sum += in[x];
-  s_part[tid] = sum;
-  __syncthreads();
-  if (tid == 0) {
-    int run = 0;
-    for (int t = 0; t < kScanThreads; ++t) {
-      const int v = s_part[t];
-      s_part[t] = run;
-      run += v;
-    }
-    out[n] = run;
+  // exclusive scan of the per-thread sums: within each wave by shuffles, then across waves
+  const int lane = tid & 63, wv = tid >> 6;
+  int incl = sum;
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {
+    const int up = __shfl_up(incl, o, kWave);
+    if (lane >= o) incl += up;
   }
+  __shared__ int s_wave[kScanThreads / kWave];
+  if (lane == kWave - 1) s_wave[wv] = incl;
   __syncthreads();
-  int run = s_part[tid];
+  int before = 0, total = 0;
+#pragma unroll
+  for (int w = 0; w < kScanThreads / kWave; ++w) {
+    if (w < wv) before += s_wave[w];
+    total += s_wave[w];
+  }
+  if (tid == 0) out[n] = total;
+  int run = before + incl - sum;
   for (int x = lo; x < hi; ++x) {
     const int v = in[x];
     out[x] = run;
@@ -210,7 +215,10 @@ __device__ __forceinline__ void gemm_wait_vmem() {
 
 // Waits until at most n of this wave's loads are outstanding (n = whole steps of 3 or 4 loads).
 __device__ __forceinline__ void gemm_wait_outstanding(int n) {
-  if (n >= 8) gemm_wait_vmem<8>();
+  if (n >= 16) gemm_wait_vmem<16>();
+  else if (n >= 12) gemm_wait_vmem<12>();
+  else if (n >= 9) gemm_wait_vmem<9>();
+  else if (n >= 8) gemm_wait_vmem<8>();
   else if (n >= 6) gemm_wait_vmem<6>();
   else if (n >= 4) gemm_wait_vmem<4>();
   else if (n >= 3) gemm_wait_vmem<3>();
@@ -336,8 +344,10 @@ __device__ __forceinline__ void early_head_tile(
 
   const int n_steps = hidden / kBK;
   // The ring: the step being multiplied, the next one (already landed, its first fragments
-  // are read before this step ends) and kStages-2 steps in flight.
-  const int n_pro = n_steps < kStages - 1 ? n_steps : kStages - 1;
+  // are read before this step ends) and kStages-2 steps in flight; the slot of the step
+  // being multiplied is handed back to the loads as soon as its last fragments are in
+  // registers, half a step before the step ends.
+  const int n_pro = n_steps < kStages ? n_steps : kStages;
   int slot_ld = 0;
   for (int i = 0; i < n_pro; ++i) {
     issue(slot_ld);
@@ -354,20 +364,20 @@ __device__ __forceinline__ void early_head_tile(
     gemm_wait_frag<kReads>(f0);  // the reads just issued fly while the MFMAs below run
     mma(f0);
     __builtin_amdgcn_sched_barrier(0);
-    // the next step has landed once at most the steps after it (kStages-3 of them were
+    gemm_wait_frag<0>(f1);  // this wave is done with the slot of this step
+    // the next step has landed once at most the steps after it (kStages-2 of them were
     // issued) are outstanding
     {
-      const int issued_after = n_steps - 2 - step < kStages - 3 ? n_steps - 2 - step : kStages - 3;
+      const int issued_after = n_steps - 2 - step < kStages - 2 ? n_steps - 2 - step : kStages - 2;
       gemm_wait_outstanding(issued_after * per_step);
     }
-    __builtin_amdgcn_s_barrier();  // it is visible; every wave is done reading step-1
-    if (step + kStages - 1 < n_steps) {
-      issue(slot_ld);  // into the slot of step-1
+    __builtin_amdgcn_s_barrier();  // it is visible; every wave is done with this step's slot
+    if (step + kStages < n_steps) {
+      issue(slot_ld);  // into the slot of this step
       slot_ld = slot_ld + 1 == kStages ? 0 : slot_ld + 1;
     }
     so = so + kStageBytes == kStages * kStageBytes ? 0 : so + kStageBytes;
     read(f0, so, 0);
-    gemm_wait_frag<kReads>(f1);
     mma(f1);
     __builtin_amdgcn_sched_barrier(0);
   }
