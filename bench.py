@@ -33,7 +33,8 @@ def log(msg: str) -> None:
 
 
 def build_inputs(w, synth):
-    """Host-side seeded inputs of one workload ('Synthetic inputs')."""
+    """Host-side seeded inputs of one workload: rank-product trees, sequence lengths, q / K / V,
+    early-head tensors with token ids placed for a given pass rate, final-layer logits."""
     t0 = time.time()
     seq_lens = synth.workload_seq_lens(w)
     trees = synth.workload_trees(w)
@@ -150,7 +151,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; nothing here uses a second one "
-              "(sequences and heads shard with no exchange, see DESIGN.md). Use --gpus 1.",
+              "(sequences and heads would shard with no exchange). Use --gpus 1.",
               file=sys.stderr)
         return 2
 
