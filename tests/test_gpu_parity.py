@@ -606,3 +606,24 @@ def test_prob_prune_token_outside_vocabulary_goes(pb):
     assert to_host(res.orig_index)[1, :4].tolist() == [0, 1, 3, 4]
     lm = to_host(res.log_marginal)
     assert np.isneginf(lm[0, 3:6]).all() and np.isneginf(lm[1, 2]) and np.isfinite(lm[1, [1, 3, 4]]).all()
+
+
+# ------------------------------------------------------------------ pruning: degenerate shapes
+
+
+def test_prune_root_only_trees_and_odd_step_count(pb, oracle):
+    """No parent rows at all (every tree is its root), then a batch that mixes root-only trees with
+    ordinary ones at a hidden size that gives an odd number of K steps (96 = 3 x 32)."""
+    w = synth.Workload(96, "case", "bf16", 3, 1, 128, 16, 96, 130, 3, 1e-3)
+    x = synth.make_prune_inputs(w, trees=[synth.chain_tree(1)] * 3)
+    res, _ = run_prune(pb, x)
+    assert to_host(res.n_kept).tolist() == [1, 1, 1] and to_host(res.cu_nodes).tolist() == [0, 1, 2, 3]
+    assert (to_host(res.new_index)[:, 0] == 0).all() and (to_host(res.new_index)[:, 1:] == -1).all()
+    res, _ = run_prob(pb, x, threshold=0.5)
+    assert to_host(res.n_kept).tolist() == [1, 1, 1]
+    rng = np.random.default_rng(96)
+    x = synth.make_prune_inputs(w, trees=[synth.chain_tree(1), synth.rank_product_tree(16, 3),
+                                         synth.random_tree(rng, 9)])
+    res, sents = run_prune(pb, x, [x["hidden_states"]])
+    ref, _ = check_prune(oracle, x, res, [x["hidden_states"]], sents)
+    assert ref["n_kept"][0] == 1 and ref["n_kept"][1] > 1
