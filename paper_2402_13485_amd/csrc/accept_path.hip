@@ -48,8 +48,8 @@ __global__ __launch_bounds__(kArgmaxThreads) void row_argmax_kernel(
     if (tid < head) argmax_next(bf16_bits_to_f32(p[tid]), tid, bv, bi);
     const int nvec = (vocab - head) >> 3;
     const u32x4 *pv = reinterpret_cast<const u32x4 *>(p + head);
-    // four independent loads in flight per lane before any of them is used
-    constexpr int kInFlight = 4;
+    // eight independent loads in flight per lane before any of them is used
+    constexpr int kInFlight = 8;
     for (int c0 = tid; c0 < nvec; c0 += kInFlight * kArgmaxThreads) {
       u32x4 u[kInFlight];
 #pragma unroll

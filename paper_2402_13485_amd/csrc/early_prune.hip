@@ -130,15 +130,35 @@ __device__ void block_exclusive_scan(const int32_t *__restrict__ in, int32_t *__
   }
 }
 
+// Row table: row_base = exclusive prefix of n_par over the sequences (workgroup 0 writes it),
+// row_src[row_base[b] + r] = node of the r-th parent of sequence b.  Every workgroup takes 256
+// (sequence, r) slots and finds the base of its first sequence by a sum of its own, so the
+// table is built by as many workgroups as there are slots instead of one.
 __global__ __launch_bounds__(kScanThreads) void row_table_kernel(
     int B, int T_max, const int32_t *__restrict__ n_par, const int32_t *__restrict__ local_list,
     int32_t *__restrict__ row_base, int32_t *__restrict__ row_src) {
-  block_exclusive_scan(n_par, row_base, B);
-  __syncthreads();
-  for (int idx = threadIdx.x; idx < B * T_max; idx += kScanThreads) {
-    const int b = idx / T_max, r = idx - b * T_max;
-    if (r < n_par[b]) row_src[row_base[b] + r] = b * T_max + local_list[idx];
+  const int tid = threadIdx.x;
+  if (blockIdx.x == 0) {
+    block_exclusive_scan(n_par, row_base, B);
+    __syncthreads();
   }
+  const int idx0 = blockIdx.x * kScanThreads;
+  const int b_first = idx0 / T_max;
+  int part = 0;
+  for (int x = tid; x < b_first; x += kScanThreads) part += n_par[x];
+  part = wave_reduce_sum(part);
+  __shared__ int s_sum[kScanThreads / kWave];
+  if ((tid & 63) == 0) s_sum[tid >> 6] = part;
+  __syncthreads();
+  int base = 0;
+#pragma unroll
+  for (int w = 0; w < kScanThreads / kWave; ++w) base += s_sum[w];
+  const int idx = idx0 + tid;
+  if (idx >= B * T_max) return;
+  const int b = idx / T_max, r = idx - b * T_max;
+  if (r >= n_par[b]) return;
+  for (int x = b_first; x < b; ++x) base += n_par[x];
+  row_src[base + r] = b * T_max + local_list[idx];
 }
 
 __global__ __launch_bounds__(kScanThreads) void cu_nodes_kernel(int B,
@@ -803,6 +823,30 @@ __global__ __launch_bounds__(kGatherThreads) void gather_rows_kernel(
   char *dbase = args.dst[pl] + b * args.stride_b[pl] + o * args.stride_outer[pl];
   const unsigned long long first =
       ((unsigned long long)slice * kGatherItems) * kGatherThreads + threadIdx.x;
+  if (args.vec16[pl] && (unsigned long long)T_max * per_row < (1ull << 31)) {
+    // the common case: 16-byte pieces, 32-bit index arithmetic, all loads of the thread's
+    // pieces in flight before the first store (items past the end re-read piece 0)
+    const unsigned per32 = (unsigned)per_row, items32 = (unsigned)items, first32 = (unsigned)first;
+    u32x4 v[kGatherItems];
+    char *dptr[kGatherItems];
+    bool ok[kGatherItems];
+#pragma unroll
+    for (int k = 0; k < kGatherItems; ++k) {
+      unsigned item = first32 + (unsigned)k * kGatherThreads;
+      ok[k] = item < items32;
+      item = ok[k] ? item : 0u;
+      const unsigned j = item / per32, c = item - j * per32;
+      int i = kept > 0 ? orig_index[(size_t)b * T_max + j] : 0;
+      ok[k] = ok[k] && i >= 0 && i < T_max;
+      i = ok[k] ? i : 0;
+      v[k] = *reinterpret_cast<const u32x4 *>(sbase + (long long)i * args.stride_t[pl] + c * 16u);
+      dptr[k] = dbase + (long long)j * args.stride_t[pl] + c * 16u;
+    }
+#pragma unroll
+    for (int k = 0; k < kGatherItems; ++k)
+      if (ok[k]) *reinterpret_cast<u32x4 *>(dptr[k]) = v[k];
+    return;
+  }
 #pragma unroll
   for (int k = 0; k < kGatherItems; ++k) {
     const unsigned long long item = first + (unsigned long long)k * kGatherThreads;
@@ -918,7 +962,8 @@ static propd_status prune_impl(
   } else {
     hipLaunchKernelGGL(parent_rows_kernel, dim3(B), dim3(PROPD_MAX_TREE), 0, st, T_max,
                        tree->n_nodes, tree->parent, ws.n_par, ws.local_list, ws.rank);
-    hipLaunchKernelGGL(row_table_kernel, dim3(1), dim3(kScanThreads), 0, st, B, T_max, ws.n_par,
+    hipLaunchKernelGGL(row_table_kernel, dim3((unsigned)((B * T_max + kScanThreads - 1) / kScanThreads)),
+                       dim3(kScanThreads), 0, st, B, T_max, ws.n_par,
                        ws.local_list, ws.row_base, ws.row_src);
     if (dt == PROPD_BF16) {
       constexpr int BM = kGemmBM, BN = 64 * kGemmMinFN;  // the grid covers the narrowest tiles
