@@ -800,7 +800,7 @@ constexpr int kGatherThreads = 256;
 // (b, o) slot and its slice of that slot's item list.  Every
 // thread moves up to kGatherItems independent pieces, so the copies of a long row (hidden
 // states) and of many short rows (tree K/V) are equally spread over the chip.
-constexpr int kGatherItems = 4;
+constexpr int kGatherItems = 8;
 
 __global__ __launch_bounds__(kGatherThreads) void gather_rows_kernel(
     PayloadArgs args, int B, int T_max, const int32_t *__restrict__ orig_index,
