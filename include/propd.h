@@ -104,6 +104,25 @@ PROPD_API propd_status propd_tree_mask(int32_t B, int32_t T_max, const int32_t *
                              void *hip_stream);
 
 /*
+ * Debug check of a tree (the other entry points trust the content of the tree arrays, see the
+ * common rules above; Section 2 defines the tree, its root and the mask).  Enqueues one small
+ * kernel that writes, for every sequence, a word of PROPD_TREE_* flags, 0 for a consistent tree:
+ *   PROPD_TREE_BAD_SIZE    n_nodes[b] outside [1, T_max]
+ *   PROPD_TREE_BAD_PARENT  parent[0] != -1, or some parent[i] outside [0, i)
+ *   PROPD_TREE_BAD_DEPTH   depth[i] is not the number of edges to the root (skipped if depth is NULL)
+ *   PROPD_TREE_BAD_MASK    anc[i] is not the set of nodes on the root path of i (skipped if anc is NULL)
+ * flags is a device array [B]; like every call it does not synchronise: read it after the stream
+ * has reached this point.  token is not looked at.
+ */
+enum {
+  PROPD_TREE_BAD_SIZE = 1,
+  PROPD_TREE_BAD_PARENT = 2,
+  PROPD_TREE_BAD_DEPTH = 4,
+  PROPD_TREE_BAD_MASK = 8
+};
+PROPD_API propd_status propd_validate_tree(const propd_tree *tree, int32_t *flags, void *hip_stream);
+
+/*
  * Tree-masked attention (Section 2, "Verification"; Figure 2(b,c)).  For every
  * sequence b, head h and tree node i < T_b:
  *     out[b,h,i,:] = softmax_j( scale * <q[b,h,i,:], k_j> ) . v_j

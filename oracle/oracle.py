@@ -121,6 +121,39 @@ def tree_attention_rows(n_nodes, parent, seq_lens, q, k_cache, v_cache, k_tree, 
     return out
 
 
+def validate_tree(n_nodes, parent, depth=None, anc=None):
+    """Flags per sequence for the debug check of a tree (Section 2: node 0 is the root, every
+    other node hangs below an earlier node; the mask row of a node is its root path):
+    1 size outside [1, T_max], 2 parent array not topological, 4 depth wrong, 8 mask wrong.
+    depth and the mask are compared with what the parent pointers give, every climb stopping
+    at a pointer that does not lead towards the root."""
+    n_nodes, parent = np.asarray(n_nodes), np.asarray(parent)
+    B, T_max = parent.shape
+    flags = np.zeros(B, np.int32)
+    for b in range(B):
+        T_raw = int(n_nodes[b])
+        if T_raw < 1 or T_raw > T_max:
+            flags[b] |= 1
+        T = min(max(T_raw, 1), T_max)
+        for i in range(T):
+            p = int(parent[b, i])
+            if (p != -1) if i == 0 else not (0 <= p < i):
+                flags[b] |= 2
+            path, x = [], i
+            while 0 <= x < T and len(path) < T:
+                path.append(x)
+                up = int(parent[b, x])
+                x = up if up < x else -1
+            if depth is not None and int(depth[b, i]) != len(path) - 1:
+                flags[b] |= 4
+            if anc is not None:
+                lo = sum(1 << x for x in path if x < 64)
+                hi = sum(1 << (x - 64) for x in path if x >= 64)
+                if int(anc[b, i, 0]) != lo or int(anc[b, i, 1]) != hi:
+                    flags[b] |= 8
+    return flags
+
+
 def early_head_rank(n_nodes, parent, token, hidden_states, head_weight, top_k):
     """-> (rank int32 [B,T_max], margin float64 [B,T_max]); head_weight is [V, Hd]."""
     hidden_states = np.ascontiguousarray(hidden_states)

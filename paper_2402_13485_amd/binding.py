@@ -23,7 +23,7 @@ WS_TREE_ATTENTION, WS_EARLY_PRUNE, WS_ACCEPT_PATH = 0, 1, 2
 MAX_TREE = 128
 MAX_PAYLOADS = 8
 
-EXPORTS = ("propd_tree_mask", "propd_tree_attention", "propd_early_prune", "propd_accept_path",
+EXPORTS = ("propd_tree_mask", "propd_validate_tree", "propd_tree_attention", "propd_early_prune", "propd_accept_path",
            "propd_early_prune_prob", "propd_commit_path", "propd_workspace_bytes", "propd_status_string",
            "propd_controller_bytes", "propd_controller_init", "propd_controller_observe_time",
            "propd_controller_observe_hit", "propd_controller_fit", "propd_controller_build_tree",
@@ -63,6 +63,8 @@ def load_library() -> ctypes.CDLL:
     vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
     lib.propd_tree_mask.restype = ctypes.c_int
     lib.propd_tree_mask.argtypes = [i32, i32, vp, vp, vp, vp, vp]
+    lib.propd_validate_tree.restype = ctypes.c_int
+    lib.propd_validate_tree.argtypes = [ctypes.POINTER(_Tree), vp, vp]
     lib.propd_tree_attention.restype = ctypes.c_int
     lib.propd_tree_attention.argtypes = [ctypes.POINTER(_Tree), ctypes.c_int, i32, i32,
                                          ctypes.c_float, vp, vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
@@ -200,6 +202,18 @@ def propd_tree_mask(n_nodes: torch.Tensor, parent: torch.Tensor):
     _check(load_library().propd_tree_mask(B, T_max, _ptr(n_nodes), _ptr(parent), _ptr(depth),
                                           _ptr(anc), _stream()), "propd_tree_mask")
     return depth, anc
+
+
+TREE_BAD_SIZE, TREE_BAD_PARENT, TREE_BAD_DEPTH, TREE_BAD_MASK = 1, 2, 4, 8
+
+
+def propd_validate_tree(tree: "Tree") -> torch.Tensor:
+    """-> int32 [B] of TREE_BAD_* flags per sequence (0 = consistent); no synchronisation."""
+    flags = torch.empty(tree.B, dtype=torch.int32, device=tree.n_nodes.device)
+    c_tree = tree._c()
+    _check(load_library().propd_validate_tree(ctypes.byref(c_tree), _ptr(flags), _stream()),
+           "propd_validate_tree")
+    return flags
 
 
 def propd_tree_attention(tree: Tree, q, k_cache, v_cache, k_tree, v_tree, seq_lens, scale: float,

@@ -26,7 +26,7 @@ def declared_entry_points():
 def test_header_declares_the_expected_calls():
     names = declared_entry_points()
     for n in ("propd_tree_attention", "propd_early_prune", "propd_accept_path", "propd_tree_mask",
-              "propd_commit_path", "propd_early_prune_prob", "propd_controller_init",
+              "propd_commit_path", "propd_early_prune_prob", "propd_validate_tree", "propd_controller_init",
               "propd_controller_best_size", "propd_workspace_bytes", "propd_status_string"):
         assert n in names
 

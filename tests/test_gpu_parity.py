@@ -627,3 +627,36 @@ def test_prune_root_only_trees_and_odd_step_count(pb, oracle):
     res, sents = run_prune(pb, x, [x["hidden_states"]])
     ref, _ = check_prune(oracle, x, res, [x["hidden_states"]], sents)
     assert ref["n_kept"][0] == 1 and ref["n_kept"][1] > 1
+
+
+# ------------------------------------------------------------------ debug check of a tree
+
+
+def test_validate_tree_matches_oracle(pb, oracle):
+    rng = np.random.default_rng(78)
+    shapes = [synth.random_tree(rng, int(T)) for T in (1, 2, 17, 70, 128, 33)]
+    n_nodes, parent, _ = synth.pad_trees(shapes, 128)
+    depth, anc = oracle.tree_mask(n_nodes, parent)
+
+    def gpu_flags(n, p, d, a):
+        tree = pb.Tree(n_nodes=to_dev(n), parent=to_dev(p), depth=None if d is None else to_dev(d),
+                       anc=None if a is None else to_dev(a))
+        f = pb.propd_validate_tree(tree)
+        torch.cuda.synchronize()
+        return to_host(f)
+
+    assert (gpu_flags(n_nodes, parent, depth, anc) == 0).all()
+    assert (gpu_flags(n_nodes, parent, None, None) == 0).all()
+    cases = []
+    n2 = n_nodes.copy(); n2[0] = 0; n2[1] = 129; n2[5] = -3
+    cases.append((n2, parent, depth, anc))
+    p2 = parent.copy(); p2[2, 0] = 0; p2[3, 5] = 5; p2[4, 9] = 40; p2[5, 7] = -1
+    cases.append((n_nodes, p2, depth, anc))
+    d2 = depth.copy(); d2[3, 69] += 1; d2[1, 1] = 0
+    cases.append((n_nodes, parent, d2, anc))
+    a2 = anc.copy(); a2[4, 100, 1] ^= np.uint64(1 << 5); a2[2, 3, 0] = np.uint64(0)
+    cases.append((n_nodes, parent, depth, a2))
+    for n, p, d, a in cases:
+        want = oracle.validate_tree(n, p, d, a)
+        assert want.any()
+        assert (gpu_flags(n, p, d, a) == want).all()

@@ -256,3 +256,23 @@ def test_rows_entry_matches_full_entry(oracle):
     with pytest.raises(ValueError):
         oracle.tree_attention_rows(x["n_nodes"], x["parent"], x["seq_lens"], x["q"], x["k_cache"],
                                    x["v_cache"], x["k_tree"], x["v_tree"], 0.5, [[1, 0, 9]])
+
+
+def test_validate_tree_flags(oracle):
+    """The debug check agrees with tree_mask on sound trees and names each kind of damage."""
+    rng = np.random.default_rng(77)
+    shapes = [synth.random_tree(rng, int(T)) for T in (1, 2, 17, 70, 128)]
+    n_nodes, parent, _ = synth.pad_trees(shapes, 128)
+    depth, anc = oracle.tree_mask(n_nodes, parent)
+    assert (oracle.validate_tree(n_nodes, parent, depth, anc) == 0).all()
+    assert (oracle.validate_tree(n_nodes, parent) == 0).all()
+    bad_n = n_nodes.copy(); bad_n[0] = 0; bad_n[1] = 129
+    f = oracle.validate_tree(bad_n, parent)
+    assert f[0] == 1 and f[1] & 1 and (f[2:] == 0).all()   # 129 nodes: padding is then read as nodes too
+    bad_p = parent.copy(); bad_p[2, 0] = 0; bad_p[3, 5] = 5; bad_p[4, 9] = 40
+    f = oracle.validate_tree(n_nodes, bad_p, depth, anc)
+    assert (f[2:] & 2).all() and (f[:2] == 0).all()
+    bad_d = depth.copy(); bad_d[3, 69] += 1
+    assert oracle.validate_tree(n_nodes, parent, bad_d, anc).tolist() == [0, 0, 0, 4, 0]
+    bad_a = anc.copy(); bad_a[4, 100, 1] ^= np.uint64(1 << 5)
+    assert oracle.validate_tree(n_nodes, parent, depth, bad_a).tolist() == [0, 0, 0, 0, 8]
