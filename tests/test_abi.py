@@ -73,7 +73,7 @@ def test_bad_scalars_are_rejected_on_the_host(pb):
         == WORKSPACE
     assert lib.propd_tree_attention(t, pb.PROPD_BF16, 0, 128, 1.0, *args, fake, 1 << 30, None) \
         == INVALID
-    # early prune: top_k < 1, hidden not a multiple of 64 for bf16, short workspace
+    # early prune: top_k < 1, hidden not a multiple of the K step for bf16, short workspace
     tout = pb._TreeOut(0x1000, 0x1000, 0x1000, 0x1000, 0x1000)
     o = ctypes.byref(tout)
     outs = (fake, fake, fake, fake, fake)
@@ -85,6 +85,28 @@ def test_bad_scalars_are_rejected_on_the_host(pb):
                                  None, fake, 16, None) == WORKSPACE
     assert lib.propd_early_prune(t, pb.PROPD_BF16, 128, 1000, 4, fake, fake, *outs, o, None, 9,
                                  None, fake, 1 << 30, None) == INVALID
+    # probability criterion: unknown mode, threshold outside [0,1], keep count below 1
+    prob = lambda mode, thr, keep, ws_bytes=1 << 30: lib.propd_early_prune_prob(
+        t, pb.PROPD_BF16, 128, 1000, mode, thr, keep, fake, fake, *outs, o, None, 0, None, fake,
+        ws_bytes, None)
+    assert prob(2, 0.5, 4) == INVALID
+    assert prob(0, 1.5, 0) == INVALID and prob(0, -0.1, 0) == INVALID
+    assert prob(0, float("nan"), 0) == INVALID
+    assert prob(1, 0.0, 0) == INVALID
+    assert prob(0, 0.5, 0, ws_bytes=16) == WORKSPACE
+    # commit: row size not a multiple of 16 bytes, misaligned pointers, missing token array
+    commit = lambda d, ptr=fake, out=fake, tr=t: lib.propd_commit_path(
+        tr, pb.PROPD_BF16, 2, d, fake, fake, 8, fake, ptr, fake, fake, fake, 64, fake, out, 8, None)
+    assert commit(12) == UNSUPPORTED
+    assert commit(128, ptr=ctypes.c_void_p(0x1008)) == INVALID
+    no_token = pb._Tree(1, 16, 0x1000, 0x1000, None, 0x1000, 0x1000)
+    assert commit(128, tr=ctypes.byref(no_token)) == INVALID
+    assert lib.propd_commit_path(t, pb.PROPD_BF16, 2, 128, fake, fake, 0, fake, fake, fake, fake,
+                                 fake, 64, fake, None, 0, None) == INVALID       # path_stride < 1
+    # debug check: needs the size and parent arrays and somewhere to write
+    assert lib.propd_validate_tree(t, None, None) == INVALID
+    no_parent = pb._Tree(1, 16, 0x1000, None, None, None, None)
+    assert lib.propd_validate_tree(ctypes.byref(no_parent), fake, None) == INVALID
     # accept: vocabulary and stride must be positive
     assert lib.propd_accept_path(t, pb.PROPD_BF16, 0, fake, fake, fake, 8, fake, fake, 1 << 20,
                                  None) == INVALID
