@@ -18,7 +18,8 @@
 //                         by testing the cached ancestor bitset against the fail
 //                         bits, order-preserving compaction by prefix popcount,
 //                         mask subsampling by bit extraction
-//   cu_nodes_kernel       exclusive prefix sum of survivor counts
+//   cu_nodes_kernel       exclusive prefix sum of survivor counts (when there are payloads
+//                         it rides along as one extra block of the gather launch)
 //   gather_rows_kernel    survivor rows of the listed payload tensors
 #include "common.h"
 
@@ -804,7 +805,14 @@ constexpr int kGatherItems = 8;
 
 __global__ __launch_bounds__(kGatherThreads) void gather_rows_kernel(
     PayloadArgs args, int B, int T_max, const int32_t *__restrict__ orig_index,
-    const int32_t *__restrict__ n_kept) {
+    const int32_t *__restrict__ n_kept, int32_t *__restrict__ cu_nodes) {
+  static_assert(kGatherThreads == kScanThreads, "the extra block runs the workgroup scan");
+  if ((long long)blockIdx.x == args.block_end[args.n - 1]) {
+    // one block past the payload blocks: the prefix sum of the survivor counts rides along
+    // with this launch instead of taking one of its own
+    block_exclusive_scan(n_kept, cu_nodes, B);
+    return;
+  }
   int pl = 0;
   while (pl < args.n - 1 && (long long)blockIdx.x >= args.block_end[pl]) ++pl;
   const long long local = (long long)blockIdx.x - (pl > 0 ? args.block_end[pl - 1] : 0);
@@ -947,7 +955,7 @@ static propd_status prune_impl(
     pa.slices[p] = (int)slices;
     total_blocks += rows * slices;
     pa.block_end[p] = total_blocks;
-    if (total_blocks > (1ll << 31) - 1) return PROPD_ERR_UNSUPPORTED;
+    if (total_blocks > (1ll << 31) - 2) return PROPD_ERR_UNSUPPORTED;
   }
   const size_t need = early_prune_workspace_bytes(B, T_max, vocab);
   if (!workspace || workspace_bytes < need) return PROPD_ERR_WORKSPACE;
@@ -1009,12 +1017,13 @@ static propd_status prune_impl(
                      tree->n_nodes, tree->parent, tree->token, tree->depth, tree->anc, ws.rank,
                      keep_bits, new_index, orig_index, n_kept, tree_out->n_nodes, tree_out->parent,
                      tree_out->token, tree_out->depth, tree_out->anc, rank_out);
-  hipLaunchKernelGGL(cu_nodes_kernel, dim3(1), dim3(kScanThreads), 0, st, B, n_kept, cu_nodes);
   if (n_payloads > 0) {
     pa.n = n_payloads;
-    dim3 grid((unsigned)total_blocks);
+    dim3 grid((unsigned)(total_blocks + 1));  // the extra block writes cu_nodes
     hipLaunchKernelGGL(gather_rows_kernel, grid, dim3(kGatherThreads), 0, st, pa, B, T_max,
-                       orig_index, n_kept);
+                       orig_index, n_kept, cu_nodes);
+  } else {
+    hipLaunchKernelGGL(cu_nodes_kernel, dim3(1), dim3(kScanThreads), 0, st, B, n_kept, cu_nodes);
   }
   return launch_ok() ? PROPD_OK : PROPD_ERR_DEVICE;
 }
