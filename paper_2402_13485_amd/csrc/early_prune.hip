@@ -501,15 +501,28 @@ __device__ __forceinline__ void rank_pass(int b, int T_max, int vocab, int c0, i
   }
   if (tid < NC) s_count[tid] = 0;
   __syncthreads();
-  for (int c = c_lo + tid; c < c_hi; c += kRankThreads) {
-    const f32x4 u = *reinterpret_cast<const f32x4 *>(z + 4 * c);
-    const int v = 4 * c;
+  // four loads of a lane in flight before the first is used (a position past the slice
+  // re-reads the slice's first vector and is not counted)
+  constexpr int kInFlight = 4;
+  for (int c0 = c_lo + tid; c0 < c_hi; c0 += kInFlight * kRankThreads) {
+    f32x4 u[kInFlight];
 #pragma unroll
-    for (int e = 0; e < NC; ++e) {
-      cnt[e] += (u.x > thr[e]) || (u.x == thr[e] && v < tok[e]);
-      cnt[e] += (u.y > thr[e]) || (u.y == thr[e] && v + 1 < tok[e]);
-      cnt[e] += (u.z > thr[e]) || (u.z == thr[e] && v + 2 < tok[e]);
-      cnt[e] += (u.w > thr[e]) || (u.w == thr[e] && v + 3 < tok[e]);
+    for (int k = 0; k < kInFlight; ++k) {
+      const int c = c0 + k * kRankThreads;
+      u[k] = *reinterpret_cast<const f32x4 *>(z + 4 * (c < c_hi ? c : c_lo));
+    }
+#pragma unroll
+    for (int k = 0; k < kInFlight; ++k) {
+      const int c = c0 + k * kRankThreads;
+      if (c >= c_hi) break;
+      const int v = 4 * c;
+#pragma unroll
+      for (int e = 0; e < NC; ++e) {
+        cnt[e] += (u[k].x > thr[e]) || (u[k].x == thr[e] && v < tok[e]);
+        cnt[e] += (u[k].y > thr[e]) || (u[k].y == thr[e] && v + 1 < tok[e]);
+        cnt[e] += (u[k].z > thr[e]) || (u[k].z == thr[e] && v + 2 < tok[e]);
+        cnt[e] += (u[k].w > thr[e]) || (u[k].w == thr[e] && v + 3 < tok[e]);
+      }
     }
   }
   if (part == kRankSplit - 1)
