@@ -85,5 +85,6 @@ inline bool launch_ok() { return hipGetLastError() == hipSuccess; }
 // scratch sizes (host arithmetic), defined next to the kernels that use the scratch
 size_t early_prune_workspace_bytes(int B, int T_max, int vocab);
 size_t tree_attention_workspace_bytes(int B, int H, int L_max, int T_max);
+size_t accept_path_workspace_bytes(int B, int T_max);
 
 }  // namespace propd

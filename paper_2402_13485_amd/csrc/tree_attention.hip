@@ -24,7 +24,8 @@
 //   - the four waves of a workgroup split the query columns (32 each); a wave whose
 //     columns lie beyond the tree only helps with the loads;
 //   - a unit cut by a range boundary leaves fp32 partials (O, max, sum), at most
-//     two per workgroup; a second kernel merges them.
+//     two per workgroup, and the workgroup holding its first piece leaves a record of the
+//     cut; a second kernel merges the pieces of every recorded cut, in their order.
 // fp32 path: a plain one-wave-per-query kernel, fp32 throughout.
 #include <type_traits>
 
@@ -50,7 +51,7 @@ struct AttnParams {
   float scale_log2e;
   float *part_o;   // [2 * grid][4 waves][16 blocks][64 lanes][4]
   float *part_ml;  // [2 * grid][4 waves][m | l][64 lanes]
-  int32_t *sched;  // [8] the schedule, left by the main kernel for the merge kernel
+  int32_t *cuts;   // [grid][4] per workgroup: the unit whose first piece it holds (CutRecord)
 };
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -254,15 +255,37 @@ struct StageMap {
   }
 };
 
-__device__ __forceinline__ long long range_start(long long w, long long n, long long g) {
-  return w * n / g;
-}
 
 struct Schedule {
   int k;                  // whole units per workgroup, done first
   long long first_split;  // first unit of the split list (= k * G)
   long long split_base;   // stages of the units before it
   long long n_split;      // stages of the split list
+  // The split list is cut into G contiguous ranges: the first `rem` workgroups take
+  // `quot` + 1 stages, the others `quot` (one division per kernel, none per range).
+  long long quot, rem;
+  __device__ __forceinline__ long long range_start(long long w) const {
+    return w * quot + (w < rem ? w : rem);
+  }
+  // workgroup whose range holds stage x of the split list
+  __device__ __forceinline__ long long range_owner(long long x) const {
+    const long long big = rem * (quot + 1);  // stages held by the larger ranges
+    if (n_split < (1ll << 31)) {             // the usual case: 32-bit divisions
+      const uint32_t xx = (uint32_t)x, bb = (uint32_t)big, qq = (uint32_t)quot;
+      return xx < bb ? xx / (qq + 1u) : (uint32_t)rem + (xx - bb) / qq;
+    }
+    return x < big ? x / (quot + 1) : rem + (x - big) / quot;
+  }
+};
+
+// What the workgroup that holds the FIRST piece of a cut unit leaves for the merge kernel
+// (every workgroup of the grid writes its record in every call; unit < 0: none).  The pieces
+// of the unit lie in workgroups w .. w_last: the first in the second partial slot of w, the
+// others in the first slot of theirs.
+struct CutRecord {
+  int32_t unit;
+  int32_t w_last_and_nodes;  // w_last | (tree nodes of the unit's sequence << 16)
+  int32_t pad[2];
 };
 
 __device__ __forceinline__ Schedule make_schedule(const StageMap &m, long long G) {
@@ -291,6 +314,8 @@ __device__ __forceinline__ Schedule make_schedule(const StageMap &m, long long G
   sc.first_split = (long long)sc.k * G;
   sc.split_base = sc.k > 0 ? m.stages_before((int)(sc.first_split / m.H), (int)(sc.first_split % m.H)) : 0;
   sc.n_split = n_all - sc.split_base;
+  sc.quot = sc.n_split / G;
+  sc.rem = sc.n_split - sc.quot * G;
   return sc;
 }
 
@@ -302,6 +327,7 @@ struct Walk {
   int whole_left;           // whole units still to do, this one included; 0 = in the split range
   long long split_unit;     // where this workgroup's split range starts
   int split_s;
+  long long x_end;          // end of this workgroup's range in the split list
   __device__ __forceinline__ void load_sizes(const StageMap &m) {
     L = m.len(b);
     T = m.nodes(b);
@@ -319,8 +345,9 @@ struct Walk {
   // the workgroup's first stage; returns the number of stages it will do
   __device__ int start(const StageMap &m, const Schedule &sc, long long w, long long G) {
     const long long U = (long long)m.B * m.H;
-    const long long x0 = range_start(w, sc.n_split, G);
-    int n_my = (int)(range_start(w + 1, sc.n_split, G) - x0);
+    const long long x0 = sc.range_start(w);
+    int n_my = (int)(sc.range_start(w + 1) - x0);
+    x_end = x0 + n_my;
     // locate stage split_base + x0 of the list of all units
     const long long x = sc.split_base + x0;
     long long b_start;
@@ -381,16 +408,16 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnPar
   const StageMap map = {p.B, p.H, p.seq_lens, p.n_nodes, p.L_max, p.T_max};
   const long long G = gridDim.x, w = blockIdx.x;
   const Schedule sch = make_schedule(map, G);
-  if (w == 0 && tid == 0) {  // the merge kernel reads the schedule instead of rebuilding it
-    p.sched[0] = sch.k;
-    p.sched[1] = 0;
-    reinterpret_cast<long long *>(p.sched)[1] = sch.first_split;
-    reinterpret_cast<long long *>(p.sched)[2] = sch.split_base;
-    reinterpret_cast<long long *>(p.sched)[3] = sch.n_split;
-  }
   Walk cp;
   const int n_my = cp.start(map, sch, w, G);
-  if (n_my <= 0) return;
+  CutRecord cut = {-1, 0, {0, 0}};
+  auto leave_record = [&]() {
+    if (tid == 0) *reinterpret_cast<CutRecord *>(p.cuts + 4 * w) = cut;
+  };
+  if (n_my <= 0) {
+    leave_record();
+    return;
+  }
 
   // ---- loader.  It walks the same stage list ahead of the math, one segment (the cached
   //      rows or the tree rows of a unit) at a time.  One direct load moves 64 lanes x 16
@@ -737,6 +764,13 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnPar
       } else {
         // a range starts inside at most one unit and ends inside at most one
         const size_t ps = 2 * (size_t)w + (s0 > 0 ? 0 : 1);
+        if (s0 == 0) {
+          // the unit starts here and runs past the end of this range, which is the end of
+          // this workgroup's work: its last stage lies us - n_st stages further
+          const int us = n_cache + (T + kStageRows - 1) / kStageRows;
+          cut.unit = done.unit;
+          cut.w_last_and_nodes = (int32_t)sch.range_owner(cp.x_end - 1 + (us - done.n_st)) | (T << 16);
+        }
         if (t < T) {
 #pragma unroll
           for (int mb = 0; mb < 4; ++mb)
@@ -753,107 +787,63 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnPar
       }
     }
   }
+  leave_record();
 }
 
 // Finish the units that a range boundary cut: out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s
-// over the workgroups s that hold a piece.  One workgroup per (unit, group of 32 queries);
-// its four waves take four pieces at a time, so that the pieces' loads are in flight
-// together, and hand their scaled parts to wave 0 through LDS.  Lanes map to (query, d)
-// exactly as in the main kernel; whole units return at once.
-__global__ __launch_bounds__(kAttnThreads) void tree_attn_combine_kernel(AttnParams p, int G) {
-  const int unit = blockIdx.x >> 2, dw = blockIdx.x & 3;
-  const int b = unit / p.H, h = unit - b * p.H;
-  const StageMap map = {p.B, p.H, p.seq_lens, p.n_nodes, p.L_max, p.T_max};
-  Schedule sch;  // as the main kernel left it
-  sch.k = uniform_load_i32(p.sched);
-  {
-    auto load64 = [&](int i) {
-      const uint32_t lo = (uint32_t)uniform_load_i32(p.sched + 2 * i);
-      const uint32_t hi = (uint32_t)uniform_load_i32(p.sched + 2 * i + 1);
-      return (long long)(((uint64_t)hi << 32) | lo);
-    };
-    sch.first_split = load64(1);
-    sch.split_base = load64(2);
-    sch.n_split = load64(3);
-  }
-  if (unit < sch.first_split) return;  // done whole by one workgroup
-  const long long n_total = sch.n_split;
-  if (n_total == 0) return;
-  const int us = map.unit_stages(b), T = map.nodes(b);
+// over the pieces s of the unit, always in the order of the pieces.  One wave per (workgroup of
+// the main kernel, group of 32 queries): it reads that workgroup's record, returns at once
+// when it names no unit, and otherwise merges the partials of workgroups w .. w_last with
+// the loads of the next piece in flight while the current one is added.  Lanes map to
+// (query, d) exactly as in the main kernel.
+__global__ __launch_bounds__(kWave) void tree_attn_combine_kernel(AttnParams p) {
+  const int w = blockIdx.x >> 2, dw = blockIdx.x & 3;
+  const CutRecord cut = *reinterpret_cast<const CutRecord *>(p.cuts + 4 * w);
+  if (cut.unit < 0) return;
+  const int T = cut.w_last_and_nodes >> 16, w_last = cut.w_last_and_nodes & 0xffff;
   if (dw * 32 >= T) return;
-  const long long S = map.stages_before(b, h) - sch.split_base;  // first stage in the split list
-  const long long E = S + us;
-  // workgroup that owns stage x: the largest w with range_start(w) <= x
-  auto owner = [&](long long x) {
-    long long w = x * G / n_total;
-    while (w + 1 < G && range_start(w + 1, n_total, G) <= x) ++w;
-    while (w > 0 && range_start(w, n_total, G) > x) --w;
-    return w;
-  };
-  const long long w_first = owner(S), w_last = owner(E - 1);
-  if (w_first == w_last) return;  // the unit was finished by one workgroup
-
-  __shared__ float s_m[4][64], s_l[4][64];
-  __shared__ f32x4 s_o[3][16][64];
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int pw = __builtin_amdgcn_readfirstlane(tid >> 6);  // piece slot of this wave
+  const int lane = threadIdx.x;
   const int t = dw * 32 + (lane & 31), g = lane >> 5;
-  f32x16 acc[4];  // running sums, used by wave 0
+  // lanes beyond the tree read lane 0's data (valid memory) and store nothing
+  const int ln = t < T ? lane : 0;
+  auto slot = [&](int wg) { return 2 * (size_t)wg + (wg == w ? 1 : 0); };
+  f32x4 o[2][16];
+  float m[2], l[2];
+  auto fetch = [&](int buf, int wg) {
+    const size_t ps = slot(wg);
+    m[buf] = p.part_ml[part_ml_index(ps, dw, 0, ln)];
+    l[buf] = p.part_ml[part_ml_index(ps, dw, 1, ln)];
+#pragma unroll
+    for (int blk = 0; blk < 16; ++blk)
+      o[buf][blk] = *reinterpret_cast<const f32x4 *>(p.part_o + part_o_index(ps, dw, blk, ln));
+  };
+  f32x16 acc[4];
 #pragma unroll
   for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[mb][r] = 0.f;
   float M = -INFINITY, lsum = 0.f;
-  for (long long base = w_first; base <= w_last; base += 4) {
-    const long long wg = base + pw;
-    // short batches leave some workgroups without any stage: they wrote no partial
-    const bool valid = wg <= w_last && range_start(wg + 1, n_total, G) > range_start(wg, n_total, G);
-    float m = -INFINITY, l = 0.f;
-    f32x4 o[16];
-    if (valid) {
-      const size_t ps = 2 * (size_t)wg + (range_start(wg, n_total, G) > S ? 0 : 1);
-      m = p.part_ml[part_ml_index(ps, dw, 0, lane)];
-      l = p.part_ml[part_ml_index(ps, dw, 1, lane)];
-#pragma unroll
-      for (int blk = 0; blk < 16; ++blk)
-        o[blk] = *reinterpret_cast<const f32x4 *>(p.part_o + part_o_index(ps, dw, blk, lane));
-    } else {
-#pragma unroll
-      for (int blk = 0; blk < 16; ++blk) o[blk] = f32x4{0.f, 0.f, 0.f, 0.f};
-    }
-    s_m[pw][lane] = m;
-    s_l[pw][lane] = l;
-    __syncthreads();
-    float M_new = M;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) M_new = fmaxf(M_new, s_m[i][lane]);
+  auto add = [&](int buf) {
+    const float M_new = fmaxf(M, m[buf]);
     const float M_safe = M_new == -INFINITY ? 0.f : M_new;
-    const float wgt = fast_exp2(m - M_safe);  // 0 for an empty slot
-    if (pw > 0) {
+    const float a_old = fast_exp2(M - M_safe), a_new = fast_exp2(m[buf] - M_safe);
+    lsum = lsum * a_old + l[buf] * a_new;
 #pragma unroll
-      for (int blk = 0; blk < 16; ++blk) s_o[pw - 1][blk][lane] = o[blk] * wgt;
-    }
-    __syncthreads();
-    if (pw == 0) {
-      const float a_old = fast_exp2(M - M_safe);
-      lsum *= a_old;
+    for (int blk = 0; blk < 16; ++blk)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) lsum += s_l[i][lane] * fast_exp2(s_m[i][lane] - M_safe);
-#pragma unroll
-      for (int blk = 0; blk < 16; ++blk) {
-        const f32x4 add = o[blk] * wgt + s_o[0][blk][lane] + s_o[1][blk][lane] + s_o[2][blk][lane];
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          acc[blk >> 2][4 * (blk & 3) + j] = acc[blk >> 2][4 * (blk & 3) + j] * a_old + add[j];
-      }
-    }
+      for (int j = 0; j < 4; ++j)
+        acc[blk >> 2][4 * (blk & 3) + j] = acc[blk >> 2][4 * (blk & 3) + j] * a_old + o[buf][blk][j] * a_new;
     M = M_new;
-    __syncthreads();  // LDS is rewritten by the next four pieces
+  };
+  fetch(0, w);
+  for (int wg = w; wg <= w_last; wg += 2) {
+    if (wg + 1 <= w_last) fetch(1, wg + 1);
+    add(0);
+    if (wg + 2 <= w_last) fetch(0, wg + 2);
+    if (wg + 1 <= w_last) add(1);
   }
-  // lanes beyond the tree read unwritten scratch and store nothing; the two lanes of an
-  // exchange pair hold the same query, so they are active together
-  if (pw == 0 && t < T)
-    store_out_row<false>(p.out + ((size_t)unit * p.T_max + t) * kD, acc, 1.f / lsum, g);
+  // the two lanes of an exchange pair hold the same query, so they are active together
+  if (t < T) store_out_row<false>(p.out + ((size_t)cut.unit * p.T_max + t) * kD, acc, 1.f / lsum, g);
 }
 
 // ------------------------------------------------------------------------------------
@@ -937,24 +927,31 @@ static int compute_units() {
   return cus;
 }
 
-// Workgroups of the persistent kernel: two per compute unit (what LDS allows to be
-// resident), fewer when the whole call has fewer than two stages per workgroup.
-static int pick_grid(int B, int H, int L_max, int T_max) {
+// Workgroups of the persistent kernel: at most one per two stages of the call, a bound the
+// host can compute without a device (the workspace is sized by it) ...
+static int grid_bound(int B, int H, int L_max, int T_max) {
   const long long per_unit = (L_max + kStageRows - 1) / kStageRows + (T_max + kStageRows - 1) / kStageRows;
   const long long stages = (long long)B * H * per_unit;
-  long long grid = 2ll * compute_units();
-  if (grid > kMaxGrid) grid = kMaxGrid;
+  long long grid = kMaxGrid;
   if (grid > (stages + 1) / 2) grid = (stages + 1) / 2;
   return (int)(grid < 1 ? 1 : grid);
 }
 
-// Partial slots: two per workgroup of the grid this call will use.
-size_t tree_attention_workspace_bytes(int B, int H, int L_max, int T_max) {
-  const size_t slots = 2 * (size_t)pick_grid(B, H, L_max, T_max);
-  return align_up(slots * kPartOFloats * 4, 256) + align_up(slots * kPartMlFloats * 4, 256) + 256;
+// ... and two per compute unit (what LDS allows to be resident).
+static int pick_grid(int B, int H, int L_max, int T_max) {
+  const int bound = grid_bound(B, H, L_max, T_max), resident = 2 * compute_units();
+  return bound < resident ? bound : resident;
 }
 
-static bool launch_bf16(const AttnParams &p, int grid, int units, hipStream_t st) {
+// Partial slots (two per workgroup) and cut records (one per workgroup) of the largest grid
+// a call with these dimensions can use.
+size_t tree_attention_workspace_bytes(int B, int H, int L_max, int T_max) {
+  const size_t grid = (size_t)grid_bound(B, H, L_max, T_max), slots = 2 * grid;
+  return align_up(slots * kPartOFloats * 4, 256) + align_up(slots * kPartMlFloats * 4, 256) +
+         align_up(grid * sizeof(CutRecord), 256);
+}
+
+static bool launch_bf16(const AttnParams &p, int grid, hipStream_t st) {
   constexpr int lds_bytes = kRingStages * kStageBytes;
   static bool attr_set = false;
   if (!attr_set) {
@@ -966,8 +963,7 @@ static bool launch_bf16(const AttnParams &p, int grid, int units, hipStream_t st
   hipLaunchKernelGGL(tree_attn_bf16_kernel<kRingStages>, dim3((unsigned)grid), dim3(kAttnThreads),
                      lds_bytes, st, p);
   if (!launch_ok()) return false;
-  hipLaunchKernelGGL(tree_attn_combine_kernel, dim3((unsigned)units * 4), dim3(kAttnThreads), 0, st, p,
-                     grid);
+  hipLaunchKernelGGL(tree_attn_combine_kernel, dim3((unsigned)grid * 4), dim3(kWave), 0, st, p);
   return launch_ok();
 }
 
@@ -1014,6 +1010,10 @@ extern "C" propd_status propd_tree_attention(const propd_tree *tree, propd_dtype
   }
 
   if (d != kD) return PROPD_ERR_UNSUPPORTED;
+  // rows are moved 16 bytes per lane, by direct loads to LDS and four-dword loads and stores
+  for (const void *ptr : {q, k_cache, v_cache, k_tree, v_tree, (const void *)out, (const void *)tree->anc,
+                          (const void *)workspace})
+    if (reinterpret_cast<uintptr_t>(ptr) % 16 != 0) return PROPD_ERR_INVALID_ARG;
   const size_t need = tree_attention_workspace_bytes(tree->B, H, L_max, tree->T_max);
   if (!workspace || workspace_bytes < need) return PROPD_ERR_WORKSPACE;
   AttnParams p;
@@ -1032,14 +1032,14 @@ extern "C" propd_status propd_tree_attention(const propd_tree *tree, propd_dtype
   p.B = tree->B;
   p.scale_log2e = scale * 1.4426950408889634f;
   const int grid = pick_grid(tree->B, H, L_max, tree->T_max);
-  const size_t slots = 2 * (size_t)grid;
-  p.part_o = reinterpret_cast<float *>(workspace);
-  p.part_ml = reinterpret_cast<float *>(reinterpret_cast<char *>(workspace) +
-                                        align_up(slots * kPartOFloats * 4, 256));
-  p.sched = reinterpret_cast<int32_t *>(reinterpret_cast<char *>(workspace) +
-                                        align_up(slots * kPartOFloats * 4, 256) +
-                                        align_up(slots * kPartMlFloats * 4, 256));
-  if (!launch_bf16(p, grid, (int)units, st)) return PROPD_ERR_DEVICE;
+  const size_t slots = 2 * (size_t)grid_bound(tree->B, H, L_max, tree->T_max);
+  char *ws = reinterpret_cast<char *>(workspace);
+  p.part_o = reinterpret_cast<float *>(ws);
+  ws += align_up(slots * kPartOFloats * 4, 256);
+  p.part_ml = reinterpret_cast<float *>(ws);
+  ws += align_up(slots * kPartMlFloats * 4, 256);
+  p.cuts = reinterpret_cast<int32_t *>(ws);
+  if (!launch_bf16(p, grid, st)) return PROPD_ERR_DEVICE;
   return PROPD_OK;
 }
 
@@ -1056,7 +1056,7 @@ extern "C" size_t propd_workspace_bytes(propd_ws_kind which, int32_t B, int32_t 
       if (vocab < 1) return 0;
       return propd::early_prune_workspace_bytes(B, T_max, vocab);
     case PROPD_WS_ACCEPT_PATH:
-      return propd::align_up((size_t)B * T_max * 4, 256);
+      return propd::accept_path_workspace_bytes(B, T_max);
   }
   return 0;
 }

@@ -48,7 +48,7 @@ def test_workspace_sizes(pb):
     assert pb.workspace_bytes(pb.WS_TREE_ATTENTION, 16, 128, 40, 128, 4096) > 0
     big = pb.workspace_bytes(pb.WS_EARLY_PRUNE, 16, 128, hidden=5120, vocab=32000)
     assert big >= 16 * 127 * 32000 * 4  # fp32 scores for every node that can have children
-    assert pb.workspace_bytes(pb.WS_ACCEPT_PATH, 16, 128, vocab=32000) >= 16 * 128 * 4
+    assert pb.workspace_bytes(pb.WS_ACCEPT_PATH, 16, 128, vocab=32000) >= 16 * 128 * 8
     assert pb.workspace_bytes(pb.WS_ACCEPT_PATH, 16, 129, vocab=32000) == 0  # tree too large
     assert pb.workspace_bytes(7, 16, 128) == 0
 

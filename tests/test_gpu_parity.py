@@ -341,6 +341,33 @@ def test_accept_ties_pick_lowest_index(pb, oracle):
             assert (g == r).all()
 
 
+def test_accept_short_path_buffer_keeps_a_prefix(pb, oracle):
+    """A path buffer shorter than the accepted path: the first path_stride nodes of the oracle's
+    path, and the token that follows them on that path as the next token (the same greedy
+    output, fewer tokens per step)."""
+    rng = np.random.default_rng(35)
+    V, T_max = 2000, 40
+    shapes = [synth.chain_tree(int(T)) for T in (40, 7, 1, 23)] + [synth.random_tree(rng, 40, max_depth=12)]
+    n_nodes, parent, _ = synth.pad_trees(shapes, T_max)
+    token = synth.draw_tokens(rng, n_nodes, parent, V)
+    logits = rng.standard_normal((len(shapes), T_max, V)).astype(np.float32)
+    for b in range(len(shapes)):                      # every child carries its parent's greedy choice
+        for i in range(1, int(n_nodes[b])):
+            logits[b, parent[b, i], token[b, i]] = 9.0 + 0.01 * (i == 1 or parent[b, i] != parent[b, i - 1])
+    full = oracle.accept_path(n_nodes, parent, token, logits, path_stride=T_max)
+    assert full[0].max() >= 12
+    for stride in (1, 4, 11):
+        alen, path, nxt = run_accept(pb, n_nodes, parent, token, logits, path_stride=stride)
+        for b in range(len(shapes)):
+            a = int(full[0][b])
+            if a <= stride:
+                assert alen[b] == a and nxt[b] == full[2][b]
+                assert (path[b] == full[1][b, :stride]).all()
+            else:
+                assert alen[b] == stride and (path[b] == full[1][b, :stride]).all()
+                assert nxt[b] == token[b, full[1][b, stride]]
+
+
 # ------------------------------------------------------------------ whole step, reduced size
 
 
