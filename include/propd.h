@@ -162,7 +162,7 @@ PROPD_API propd_status propd_tree_attention(const propd_tree *tree, propd_dtype 
  *   hidden_states [B,T_max,hidden]  layer-n hidden state of every tree token
  *   head_weight   [vocab,hidden]    weight of the bias-free early head, one row
  *                                   per vocabulary entry (nn.Linear layout)
- *   dt            PROPD_BF16 (hidden must be a multiple of 64) or PROPD_F32
+ *   dt            PROPD_BF16 (hidden must be a multiple of 32) or PROPD_F32
  *   tree          all five arrays are read; token ids outside [0, vocab) fail
  * Outputs (each fully written, padding included; any may NOT alias an input):
  *   keep_bits  [B,2]      bit i set iff node i survives
@@ -173,12 +173,17 @@ PROPD_API propd_status propd_tree_attention(const propd_tree *tree, propd_dtype 
  *   tree_out   compacted tree in the same padded layout, survivors first:
  *              parent re-indexed, token and depth copied, anc subsampled;
  *              slots >= n_kept[b] hold -1 (anc: 0)
- *   rank_out   [B,T_max] or NULL: rank_c as counted (root 0, padding -1); ranks of
- *              near-equal scores may differ from a higher-precision evaluation
+ *   rank_out   [B,T_max] or NULL: rank_c as counted (root 0, padding -1, vocab for a token
+ *              id outside the vocabulary); ranks of near-equal scores may differ from a
+ *              higher-precision evaluation
  *   payloads   host array of n_payloads descriptors (0..PROPD_MAX_PAYLOADS, read
  *              during the call only).  Row (b,o,orig_index[b,j]) of src is copied
  *              to row (b,o,j) of dst for j < n_kept[b]; other dst rows are untouched.
- *   workspace  propd_workspace_bytes(PROPD_WS_EARLY_PRUNE, ...) bytes
+ *   workspace  propd_workspace_bytes(PROPD_WS_EARLY_PRUNE, ...) bytes, 16-byte aligned.  The
+ *              scores themselves are never stored: the scratch holds per-node tables and,
+ *              for the probability criterion, two floats per score row and 64 columns.
+ * hidden_states and head_weight must be 16-byte aligned for PROPD_BF16
+ * (PROPD_ERR_INVALID_ARG otherwise).
  */
 #define PROPD_MAX_PAYLOADS 8
 PROPD_API propd_status propd_early_prune(const propd_tree *tree, propd_dtype dt, int32_t hidden,
@@ -336,7 +341,9 @@ PROPD_API propd_status propd_controller_best_size(const void *state, double now,
                                double *speed, double *beta0, double *beta1);
 
 /* Workspace size in bytes for one call with these dimensions (arguments a call
- * does not have are ignored).  Pure host arithmetic.  Returns 0 for a bad `which`. */
+ * does not have are ignored).  Pure host arithmetic: no device is queried, so the size is
+ * the same on every machine and a size asked for before a call is accepted by that call.
+ * Returns 0 for a bad `which`. */
 typedef enum {
   PROPD_WS_TREE_ATTENTION = 0,
   PROPD_WS_EARLY_PRUNE = 1,

@@ -1,26 +1,36 @@
-// Early pruning of the token tree (Section 4.1: "Pruning Process" and
+// Early pruning of the token tree (Section 4.1: "Pruning Process", "Pruning Criterion" and
 // "Implementation Optimization").
 //
 // Kernel chain, all on the caller's stream, no host round trip:
-//   parent_rows_kernel    per sequence: which nodes have children (only those
-//                         need early-head scores), compacted by wave ballot
-//   row_table_kernel      prefix sum over sequences -> global row table
-//   early_head_bf16_kernel  scores z = hidden[parent rows] . head_weight^T as a
-//                         bf16 MFMA GEMM with fp32 accumulation (M = parent rows,
-//                         N = vocabulary, K = hidden); fp32 scores go to scratch
-//   early_head_f32_kernel plain fp32 variant
-//   rank_count_kernel     per parent row: rank of every child's token by
-//                         counting scores that beat it (the top-k membership test)
-//   child_logprob_kernel  probability criterion: log-sum-exp of every parent row and the
-//                         log-probability of every child's token
-//   prob_decide_kernel    probability criterion: path marginals, threshold or rank test
-//   prune_compact_kernel  per sequence: fail bits by ballot, branch elimination
-//                         by testing the cached ancestor bitset against the fail
-//                         bits, order-preserving compaction by prefix popcount,
-//                         mask subsampling by bit extraction
+//   prune_prepare_kernel  one launch, two kinds of workgroups.  Workgroup 0: which nodes have
+//                         children (only those need early-head scores), the table of score
+//                         rows, and every node's children grouped by parent.  The others:
+//                         each child's OWN score z_p[tok_c], 8 children per workgroup, by the
+//                         same chain of matrix instructions that the scoring kernel runs for
+//                         that element, so the two values are the same bits
+//   early_head_bf16_kernel  scores z = hidden[parent rows] . head_weight^T as a bf16 MFMA
+//                         GEMM with fp32 accumulation (M = parent rows, N = vocabulary,
+//                         K = hidden).  The scores never leave the registers: the epilogue
+//                         compares every score of a row with the own scores of that row's
+//                         children and leaves, per child and column tile, the count of scores
+//                         that beat it (the top-k membership test; plain stores, every slot
+//                         written exactly once, so the sums do not depend on any order), or, for the
+//                         probability criterion, leaves (max, sum of exponentials) per row
+//                         and column tile
+//   early_head_f32_kernel plain fp32 variant with the same epilogue
+//   row_lse_kernel        probability criterion: log-sum-exp of every row from the tile
+//                         partials, log-probability of every child's token
+//   prune_compact_kernel  per sequence: the criterion's decision per node (rank against k, or
+//                         path marginal against the threshold / the keep count), fail bits by
+//                         ballot, branch elimination by testing the cached ancestor bitset
+//                         against the fail bits, order-preserving compaction by prefix
+//                         popcount, mask subsampling by bit extraction
 //   cu_nodes_kernel       exclusive prefix sum of survivor counts (when there are payloads
 //                         it rides along as one extra block of the gather launch)
 //   gather_rows_kernel    survivor rows of the listed payload tensors
+#include <type_traits>
+#include <utility>
+
 #include "common.h"
 
 namespace propd {
@@ -29,14 +39,20 @@ namespace propd {
 // scratch layout
 // ------------------------------------------------------------------------------------
 struct PruneScratch {
-  int32_t *rank;        // [B*T_max]
-  int32_t *n_par;       // [B]
+  int32_t *n_par;       // [B]        nodes with children
   int32_t *local_list;  // [B*T_max]  per sequence: nodes with children, ascending
-  int32_t *row_src;     // [B*T_max]  global row -> b*T_max + node
+  int32_t *row_src;     // [B*T_max]  score row -> b*T_max + node
   int32_t *row_base;    // [B+1]      exclusive prefix of n_par; [B] = total rows
+  int32_t *row_info;    // [B*T_max][2] score row -> (first position in child_list, children)
+  int32_t *child_pos;   // [B*T_max]  node -> first position of its children in child_list
+  int32_t *child_cnt;   // [B*T_max]  node -> number of children
+  int32_t *child_list;  // [B*T_max]  b*T_max + child, grouped by parent, per sequence slot
+  float *own;           // [B*T_max]  z_parent[token] of every non-root node
   float *logq;          // [B*T_max]  probability criterion: log q of every node's token
-  float *scores;        // [row_cap * score_pitch]
-  size_t row_cap, score_pitch, total_bytes;
+  float *lse_part;      // [row_cap * parts][2]  probability criterion: (max, sum exp) per tile
+  int32_t *cnt_part;    // [parts / 2][B*T_max]  top-k criterion: per column tile, the scores of the
+                        //                       parent's row that beat the node's token
+  size_t row_cap, parts, total_bytes;
 };
 
 static PruneScratch carve_scratch(void *base, int B, int T_max, int vocab) {
@@ -49,15 +65,22 @@ static PruneScratch carve_scratch(void *base, int B, int T_max, int vocab) {
     off += align_up(bytes, 256);
     return q;
   };
-  s.rank = reinterpret_cast<int32_t *>(take(nt * 4));
   s.n_par = reinterpret_cast<int32_t *>(take((size_t)B * 4));
   s.local_list = reinterpret_cast<int32_t *>(take(nt * 4));
   s.row_src = reinterpret_cast<int32_t *>(take(nt * 4));
   s.row_base = reinterpret_cast<int32_t *>(take((size_t)(B + 1) * 4));
+  s.row_info = reinterpret_cast<int32_t *>(take(nt * 8));
+  s.child_pos = reinterpret_cast<int32_t *>(take(nt * 4));
+  s.child_cnt = reinterpret_cast<int32_t *>(take(nt * 4));
+  s.child_list = reinterpret_cast<int32_t *>(take(nt * 4));
+  s.own = reinterpret_cast<float *>(take(nt * 4));
   s.logq = reinterpret_cast<float *>(take(nt * 4));
   s.row_cap = (size_t)B * (T_max > 1 ? T_max - 1 : 1);  // a node with children is not a leaf
-  s.score_pitch = align_up((size_t)vocab, 4);
-  s.scores = reinterpret_cast<float *>(take(s.row_cap * s.score_pitch * 4));
+  // column parts of a row: two per 128-wide tile (the narrowest MFMA tile, one per wave
+  // column), which also covers the 256-wide slices of the fp32 kernel
+  s.parts = 2 * (((size_t)vocab + 127) / 128);
+  s.lse_part = reinterpret_cast<float *>(take(s.row_cap * s.parts * 8));
+  s.cnt_part = reinterpret_cast<int32_t *>(take((s.parts / 2) * nt * 4));
   s.total_bytes = off;
   return s;
 }
@@ -66,34 +89,7 @@ size_t early_prune_workspace_bytes(int B, int T_max, int vocab) {
   return carve_scratch(nullptr, B, T_max, vocab).total_bytes;
 }
 
-// ------------------------------------------------------------------------------------
-// which nodes need scores
-// ------------------------------------------------------------------------------------
-__global__ __launch_bounds__(PROPD_MAX_TREE) void parent_rows_kernel(
-    int T_max, const int32_t *__restrict__ n_nodes, const int32_t *__restrict__ parent,
-    int32_t *__restrict__ n_par, int32_t *__restrict__ local_list, int32_t *__restrict__ rank) {
-  const int b = blockIdx.x, i = threadIdx.x;
-  int T = n_nodes[b];
-  T = T < 1 ? 1 : (T > T_max ? T_max : T);
-  __shared__ int s_has_child[PROPD_MAX_TREE];
-  __shared__ int s_wave_count[2];
-  s_has_child[i] = 0;
-  __syncthreads();
-  if (i > 0 && i < T) {
-    const int p = parent[(size_t)b * T_max + i];
-    if (p >= 0 && p < i) s_has_child[p] = 1;  // same value from every child: benign
-  }
-  __syncthreads();
-  const bool is_par = i < T && s_has_child[i] != 0;
-  const uint64_t bal = __ballot(is_par);
-  if ((i & 63) == 0) s_wave_count[i >> 6] = __popcll(bal);
-  __syncthreads();
-  const int before = (i >= 64 ? s_wave_count[0] : 0) + __popcll(bal & ((1ull << (i & 63)) - 1ull));
-  if (is_par) local_list[(size_t)b * T_max + before] = i;
-  if (i == 0) n_par[b] = s_wave_count[0] + s_wave_count[1];
-  // ranks default to 0 (root; everything when nothing is scored), padding to -1
-  if (i < T_max) rank[(size_t)b * T_max + i] = i < T ? 0 : -1;
-}
+__device__ __forceinline__ int clamp_tree(int T, int T_max) { return T < 1 ? 1 : (T > T_max ? T_max : T); }
 
 constexpr int kScanThreads = 256;
 
@@ -131,42 +127,230 @@ __device__ void block_exclusive_scan(const int32_t *__restrict__ in, int32_t *__
   }
 }
 
-// Row table: row_base = exclusive prefix of n_par over the sequences (workgroup 0 writes it),
-// row_src[row_base[b] + r] = node of the r-th parent of sequence b.  Every workgroup takes 256
-// (sequence, r) slots and finds the base of its first sequence by a sum of its own, so the
-// table is built by as many workgroups as there are slots instead of one.
-__global__ __launch_bounds__(kScanThreads) void row_table_kernel(
-    int B, int T_max, const int32_t *__restrict__ n_par, const int32_t *__restrict__ local_list,
-    int32_t *__restrict__ row_base, int32_t *__restrict__ row_src) {
-  const int tid = threadIdx.x;
-  if (blockIdx.x == 0) {
-    block_exclusive_scan(n_par, row_base, B);
-    __syncthreads();
-  }
-  const int idx0 = blockIdx.x * kScanThreads;
-  const int b_first = idx0 / T_max;
-  int part = 0;
-  for (int x = tid; x < b_first; x += kScanThreads) part += n_par[x];
-  part = wave_reduce_sum(part);
-  __shared__ int s_sum[kScanThreads / kWave];
-  if ((tid & 63) == 0) s_sum[tid >> 6] = part;
-  __syncthreads();
-  int base = 0;
-#pragma unroll
-  for (int w = 0; w < kScanThreads / kWave; ++w) base += s_sum[w];
-  const int idx = idx0 + tid;
-  if (idx >= B * T_max) return;
-  const int b = idx / T_max, r = idx - b * T_max;
-  if (r >= n_par[b]) return;
-  for (int x = b_first; x < b; ++x) base += n_par[x];
-  row_src[base + r] = b * T_max + local_list[idx];
-}
-
 __global__ __launch_bounds__(kScanThreads) void cu_nodes_kernel(int B,
                                                                 const int32_t *__restrict__ n_kept,
                                                                 int32_t *__restrict__ cu_nodes) {
   block_exclusive_scan(n_kept, cu_nodes, B);
 }
+
+// ------------------------------------------------------------------------------------
+// preparation: tables (workgroup 0) and the children's own scores (the other workgroups)
+// ------------------------------------------------------------------------------------
+struct PrepareArgs {
+  int B, T_max, hidden, vocab;
+  const int32_t *n_nodes, *parent, *token;
+  const void *hidden_states, *head_weight;
+  int32_t *n_par, *local_list, *row_src, *row_base, *row_info, *child_pos, *child_cnt, *child_list;
+  float *own;
+};
+
+// One wave per sequence at a time, two nodes per lane (lane and lane + 64); everything a wave
+// needs from other lanes goes through a 128-entry array of its own in LDS, ordered by the
+// wave's own program order (LDS operations of a wave complete in order).
+__device__ __forceinline__ void wave_lds_fence() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
+__device__ void prepare_tables(const PrepareArgs &a) {
+  __shared__ int s_cnt[kScanThreads / kWave][PROPD_MAX_TREE];
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  int *cnt = s_cnt[wv];
+  for (int b = wv; b < a.B; b += kScanThreads / kWave) {
+    const int T = clamp_tree(a.n_nodes[b], a.T_max);
+    const size_t base = (size_t)b * a.T_max;
+    int node[2] = {lane, lane + 64}, par[2], slot[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      par[h] = -1;
+      if (node[h] > 0 && node[h] < T) {
+        const int p = a.parent[base + node[h]];
+        par[h] = (p >= 0 && p < node[h]) ? p : -1;  // a parent that is no earlier node: no edge
+      }
+      cnt[node[h]] = 0;
+    }
+    wave_lds_fence();
+    // children per parent; the value before the addition numbers a child among its siblings
+#pragma unroll
+    for (int h = 0; h < 2; ++h) slot[h] = par[h] >= 0 ? atomicAdd(&cnt[par[h]], 1) : 0;
+    wave_lds_fence();
+    int mine[2] = {cnt[node[0]], cnt[node[1]]};
+    wave_lds_fence();
+    // exclusive prefix of the child counts over the nodes, and of "has children"
+    int incl[2], par_before[2];
+    uint64_t has[2];
+    int run = 0, run_par = 0;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      incl[h] = mine[h];
+#pragma unroll
+      for (int o = 1; o < kWave; o <<= 1) {
+        const int up = __shfl_up(incl[h], o, kWave);
+        if (lane >= o) incl[h] += up;
+      }
+      const int total = __shfl(incl[h], 63, kWave);
+      incl[h] += run;
+      run += total;
+      has[h] = __ballot(mine[h] > 0);
+      par_before[h] = run_par + __popcll(has[h] & ((1ull << lane) - 1ull));
+      run_par += __popcll(has[h]);
+    }
+    // positions are global: b*T_max + position in the sequence's slot
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      cnt[node[h]] = incl[h] - mine[h];  // first position of this node's children
+    }
+    wave_lds_fence();
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      if (node[h] < a.T_max) {
+        a.child_pos[base + node[h]] = (int)base + incl[h] - mine[h];
+        a.child_cnt[base + node[h]] = mine[h];
+      }
+      if (par[h] >= 0) a.child_list[base + cnt[par[h]] + slot[h]] = (int)base + node[h];
+      if (mine[h] > 0) a.local_list[base + par_before[h]] = node[h];
+    }
+    if (lane == 0) a.n_par[b] = run_par;
+    wave_lds_fence();
+  }
+  __threadfence_block();
+  __syncthreads();
+  block_exclusive_scan(a.n_par, a.row_base, a.B);
+  __threadfence_block();
+  __syncthreads();
+  for (int b = wv; b < a.B; b += kScanThreads / kWave) {
+    const size_t base = (size_t)b * a.T_max;
+    const int n = a.n_par[b], first = a.row_base[b];
+    for (int r = lane; r < n; r += kWave) {
+      const int nd = a.local_list[base + r];
+      a.row_src[first + r] = (int)base + nd;
+      a.row_info[2 * (first + r)] = a.child_pos[base + nd];
+      a.row_info[2 * (first + r) + 1] = a.child_cnt[base + nd];
+    }
+  }
+}
+
+// The children's own scores, bf16: workgroup (b, group) takes nodes 8*group .. +7 of
+// sequence b (few nodes per workgroup: the rows are fetched once, from all over the weight
+// matrix, and it is the number of workgroups that brings the bytes in flight).  Tile rows:
+// A row j = hidden state of the parent of node j, B row j = weight row of node j's token; the
+// diagonal of A . B^T holds the scores wanted (rows 8..31 of the 32-row tile repeat rows
+// 0..7).  All four waves fetch (coalesced, eight 256-deep steps ahead, through registers into
+// a padded double buffer in LDS); wave 0 runs the chain of 32x32x16 matrix instructions over
+// K in rising order, starting from zero: the chain the scoring kernel runs for every element
+// of its tiles.
+constexpr int kOwnNodes = 8;                      // children per workgroup
+constexpr int kOwnStep = 256;                     // K per fetch step
+constexpr int kOwnRowBytes = kOwnStep * 2 + 16;   // padded: the 8 rows start 4 banks apart
+constexpr int kOwnAhead = 8;
+
+__device__ void own_scores_bf16(const PrepareArgs &a, int b, int group) {
+  __shared__ __attribute__((aligned(16))) unsigned char s_tile[2][2][kOwnNodes * kOwnRowBytes];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int T = clamp_tree(a.n_nodes[b], a.T_max);
+  if (kOwnNodes * group >= T) return;  // uniform over the workgroup
+  const size_t base = (size_t)b * a.T_max;
+  // loader: thread -> (row, 16-byte piece of the step's 512 bytes)
+  const int ld_row = tid >> 5, ld_piece = tid & 31;
+  int nd = kOwnNodes * group + ld_row;
+  nd = nd < T ? nd : T - 1;
+  int p = nd > 0 ? a.parent[base + nd] : 0;
+  p = (p >= 0 && p < T) ? p : 0;
+  int tk = a.token[base + nd];
+  tk = (tk >= 0 && tk < a.vocab) ? tk : 0;
+  const uint16_t *a_src = reinterpret_cast<const uint16_t *>(a.hidden_states) + (base + p) * (size_t)a.hidden + ld_piece * 8;
+  const uint16_t *b_src = reinterpret_cast<const uint16_t *>(a.head_weight) + (size_t)tk * a.hidden + ld_piece * 8;
+  const int n_steps = (a.hidden + kOwnStep - 1) / kOwnStep;
+  const int n_k16 = a.hidden / 16;
+  u32x4 ra[kOwnAhead], rb[kOwnAhead];
+  auto fetch = [&](int slot, int step) {
+    const bool in = step < n_steps && step * kOwnStep + ld_piece * 8 < a.hidden;
+    const int off = in ? step * kOwnStep : 0;
+    ra[slot] = *reinterpret_cast<const u32x4 *>(a_src + off);
+    rb[slot] = *reinterpret_cast<const u32x4 *>(b_src + off);
+  };
+#pragma unroll
+  for (int i = 0; i < kOwnAhead; ++i) fetch(i, i);
+  f32x16 acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  const int l32 = lane & 31, g = lane >> 5;
+  const int frag_off = (l32 & (kOwnNodes - 1)) * kOwnRowBytes + g * 16;
+  for (int s0 = 0; s0 < n_steps; s0 += kOwnAhead) {
+#pragma unroll
+    for (int i = 0; i < kOwnAhead; ++i) {
+      const int step = s0 + i;
+      if (step >= n_steps) break;  // uniform
+      unsigned char *buf_a = s_tile[step & 1][0], *buf_b = s_tile[step & 1][1];
+      *reinterpret_cast<u32x4 *>(buf_a + ld_row * kOwnRowBytes + ld_piece * 16) = ra[i];
+      *reinterpret_cast<u32x4 *>(buf_b + ld_row * kOwnRowBytes + ld_piece * 16) = rb[i];
+      fetch(i, step + kOwnAhead);
+      __syncthreads();  // the step is in LDS; wave 0 is done with the other buffer
+      if (wave == 0) {
+        const int k16_left = n_k16 - step * (kOwnStep / 16);
+#pragma unroll
+        for (int ks = 0; ks < kOwnStep / 16; ++ks) {
+          if (ks < k16_left) {
+            const bf16x8 fa = *reinterpret_cast<const bf16x8 *>(buf_a + frag_off + ks * 32);
+            const bf16x8 fb = *reinterpret_cast<const bf16x8 *>(buf_b + frag_off + ks * 32);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc, 0, 0, 0);
+          }
+        }
+      }
+    }
+  }
+  if (wave != 0) return;
+  mfma_settle();
+  // element (row, col) of the tile sits in lane col + 32*g, register r, with
+  // row = 8*(r/4) + 4*g + r%4: the diagonal element of column j < 8 is in the half
+  // g = j >> 2, register j & 3
+  float diag = 0.f;
+#pragma unroll
+  for (int r = 0; r < 4; ++r)
+    if (r == (l32 & 3)) diag = acc[r];
+  const int my_node = kOwnNodes * group + l32;
+  if (l32 < kOwnNodes && g == (l32 >> 2) && my_node > 0 && my_node < T) a.own[base + my_node] = diag;
+}
+
+// fp32: one lane per node, the same sequential fused multiply-add chain as the scoring kernel
+__device__ void own_scores_f32(const PrepareArgs &a, int b, int group) {
+  const int T = clamp_tree(a.n_nodes[b], a.T_max);
+  const int nd = kOwnNodes * group + (int)threadIdx.x;
+  if (threadIdx.x >= kOwnNodes || nd < 1 || nd >= T) return;
+  const size_t base = (size_t)b * a.T_max;
+  int p = a.parent[base + nd];
+  p = (p >= 0 && p < T) ? p : 0;
+  int tk = a.token[base + nd];
+  tk = (tk >= 0 && tk < a.vocab) ? tk : 0;
+  const float *h = reinterpret_cast<const float *>(a.hidden_states) + (base + p) * (size_t)a.hidden;
+  const float *w = reinterpret_cast<const float *>(a.head_weight) + (size_t)tk * a.hidden;
+  float acc = 0.f;
+  for (int x = 0; x < a.hidden; ++x) acc = fmaf(h[x], w[x], acc);
+  a.own[base + nd] = acc;
+}
+
+template <bool kBf16>
+__global__ __launch_bounds__(kScanThreads) void prune_prepare_kernel(PrepareArgs a) {
+  if (blockIdx.x == 0) {
+    prepare_tables(a);
+    return;
+  }
+  const int groups = (a.T_max + kOwnNodes - 1) / kOwnNodes;
+  const int b = (blockIdx.x - 1) / groups, group = (blockIdx.x - 1) - b * groups;
+  if (kBf16) own_scores_bf16(a, b, group);
+  else own_scores_f32(a, b, group);
+}
+
+// What the scoring kernels need besides the operands.
+struct HeadTables {
+  const int32_t *row_src, *row_base, *row_info, *child_list, *token;
+  const float *own;
+  int32_t *cnt_part;  // [column tile][cnt_stride]
+  int cnt_stride;     // B * T_max
+  float *lse_part;
+  int parts;  // column parts per row in lse_part
+};
+
+// children of a row taken per pass of the counting epilogue
+constexpr int kEpiChildren = 16;
 
 // ------------------------------------------------------------------------------------
 // early head, bf16 MFMA
@@ -180,24 +364,26 @@ __global__ __launch_bounds__(kScanThreads) void cu_nodes_kernel(int B,
 //     delivery, not by the matrix cores); FN is the width with the fewest
 //     rounds-of-workgroups x width on this chip, computed by every workgroup from the row
 //     count on the device, so the host never needs that count;
-//   - K advances 32 per step through a ring of four 32 KB LDS stages filled by direct
-//     global->LDS loads (no staging registers, no LDS stores), up to three steps ahead of
-//     the math; one barrier per K step.  A row of a stage is 64 bytes (4 chunks of 16); the
-//     lane that fills chunk c of LDS row r fetches chunk c ^ key(r) of the global row, with
-//     key(r) = (r >> 2) & 3, so that the 16 rows one quarter-wave reads for a chunk column
-//     fall into 16 different bank groups;
+//   - K advances 32 per step through a ring of LDS stages filled by direct global->LDS loads
+//     (no staging registers, no LDS stores), up to three steps ahead of the math; one barrier
+//     per K step.  A row of a stage is 64 bytes (4 chunks of 16); the lane that fills chunk c
+//     of LDS row r fetches chunk c ^ key(r) of the global row, with key(r) = (r >> 2) & 3, so
+//     that the 16 rows one quarter-wave reads for a chunk column fall into 16 different bank
+//     groups;
 //   - operand fragments are double-buffered in registers: the LDS reads of one half step
 //     are issued before the MFMAs of the half step before it, and the barrier sits between
 //     two MFMA groups whose operands are already in registers, so the matrix core has work
 //     queued while waves meet;
 //   - the A rows are gathered through the row table by the loads themselves; rows past
 //     the last one and vocabulary entries past the last re-read the last valid one and
-//     are dropped when the scores are stored;
-//   - the grid is one-dimensional and XCD-aware.  Workgroups are handed to the 8
-//     XCDs round-robin, each XCD has its own L2: workgroup id -> (xcd, slot), and an
-//     XCD walks its own vocabulary tiles with all row tiles of one vocabulary tile
-//     adjacent in time, so a weight tile is fetched from HBM once and hits in that
-//     XCD's L2 for the other row tiles.
+//     are left out by the epilogue;
+//   - the scores stay in the accumulators: the epilogue turns them into rank counts (or
+//     log-sum-exp partials) and nothing of size rows x vocabulary ever reaches memory;
+//   - the grid is one-dimensional, persistent and XCD-aware.  Workgroups are handed to the 8
+//     XCDs round-robin, each XCD has its own L2: tile id -> (xcd, slot), and an XCD walks
+//     its own vocabulary tiles with all row tiles of one vocabulary tile adjacent in time,
+//     so a weight tile is fetched from HBM once and hits in that XCD's L2 for the other
+//     row tiles.
 constexpr int kBK = 32;
 constexpr int kGemmBM = 256;
 constexpr int kGemmMinFN = 2, kGemmMaxFN = 4;
@@ -277,12 +463,261 @@ __device__ __forceinline__ void gemm_wait_frag(GemmFrag<FN> &f) {
                  : "n"(N));
 }
 
+// ---- epilogues.  Accumulator layout of the 32x32 MFMA: lane -> column l32 (+ 32 y), register
+//      r -> row 8*(r/4) + 4*g + r%4 (+ 32 x): a row of the tile lives in the 32 lanes of one
+//      half of a wave, so a ballot over a comparison counts two rows at once.
+
+// Top-k membership by counting (Section 4.1, "Pruning Criterion"): for every child c of the
+// row's node, the scores of the row that beat the child's own score (a higher score, or the
+// same score at a lower id) are counted; the count of this column tile goes to the child's
+// slot of the tile in cnt_part, and the decision kernel adds the tiles up.
+//
+// The children of the tile's rows are staged in LDS (the ring is free by now), kEpiChildren
+// per row and pass.  "Beats" is turned into one comparison per score: for the columns of a
+// wave that all lie above the child's token the threshold is the own score (z > own), for
+// columns that all lie below it the next smaller float (z > pred(own), i.e. z >= own); only
+// the one wave whose columns contain the token compares per lane, on a side path marked by
+// a NaN threshold, which the main comparison counts as nothing.  A lane walks its 32 rows
+// with the thresholds of the next row already requested, four per LDS read, counts its own
+// columns in a byte per child, and one cross-lane sum per row and four children (DPP)
+// leaves the row's counts in the last lane of each half wave.
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+
+// A loop whose index is a compile-time constant in every iteration: accumulator registers can
+// only be named by constants, and an ordinary loop this large is not always unrolled.
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f) {
+  static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+// the largest float below x (x itself for -inf and NaN): z > float_pred(x)  <=>  z >= x
+__device__ __forceinline__ float float_pred(float x) {
+  const uint32_t u = __float_as_uint(x);
+  if (x > 0.f) return __uint_as_float(u - 1u);
+  if (x == 0.f) return __uint_as_float(0x80000001u);
+  if (x < 0.f && x > -INFINITY) return __uint_as_float(u + 1u);
+  return x;
+}
+
+// Sum over the 32 lanes of each half wave, left in lanes 31 and 63.
+__device__ __forceinline__ int half_wave_sum_to_last(int v) {
+  v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);  // row_shr:1
+  v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);  // row_shr:2
+  v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);  // row_shr:4
+  v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);  // row_shr:8: lane 15 of a row = its sum
+  v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1 and 3
+  return v;
+}
+
 template <int FN>
+__device__ __forceinline__ void epilogue_count(f32x16 (&acc)[2][FN], int m0, int v0, int n_tile, int vocab,
+                                               int tid_in, int my_pos, int my_cc,
+                                               const HeadTables &tb, unsigned char *smem) {
+  constexpr int BM = kGemmBM, WN = 32 * FN, E = kEpiChildren;
+  static_assert(E % 4 == 0 && FN * 32 < 256 && kGemmThreads % E == 0, "four byte-sized counts per word");
+  // Everything below is derived from this copy of the thread id, which the compiler cannot
+  // see through: otherwise it computes the dozens of LDS addresses of this epilogue before the
+  // K loop and keeps them in scratch memory across it.
+  int tid = tid_in;
+  asm volatile("" : "+v"(tid));
+  const int lane = tid & 63, l32 = lane & 31, g = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), wm = wave >> 1, wn = wave & 1;
+  int *s_max = reinterpret_cast<int *>(smem);
+  int *s_cc = s_max + 64;                                // [BM] children of the row in this pass | flags << 8
+  int *s_pos = s_cc + BM;                                // [BM] first position in child_list
+  float *s_thr = reinterpret_cast<float *>(s_pos + BM);  // [2][BM][E] threshold per wave column
+  float *s_own = s_thr + 2 * BM * E;                     // [BM][E]
+  int *s_tok = reinterpret_cast<int *>(s_own + BM * E);  // [BM][E]
+  int *s_node = s_tok + BM * E;                          // [BM][E]
+  int *s_count = s_node + BM * E;                        // [2][BM][E/4] packed counts per wave column
+  // columns past the vocabulary (last column tile only) can beat nothing
+  if (v0 + 2 * WN > vocab) {
+#pragma unroll
+    for (int y = 0; y < FN; ++y) {
+      const bool out = v0 + wn * WN + y * 32 + l32 >= vocab;
+#pragma unroll
+      for (int x = 0; x < 2; ++x)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[x][y][r] = out ? -INFINITY : acc[x][y][r];
+    }
+  }
+  __syncthreads();  // every wave is done with the ring
+  if (tid == 0) *s_max = 0;
+  __syncthreads();
+  {
+    const int wave_max = wave_reduce_max(tid < BM ? my_cc : 0);
+    if (lane == 0 && wave_max > 0) atomicMax(s_max, wave_max);
+  }
+  __syncthreads();
+  const int max_cc = *s_max;
+  // this lane's rows: row0 + a constant per (x, r)
+  const int row0 = wm * 64 + 4 * g;
+  const int *cc_base = s_cc + row0;
+  const float *thr_base = s_thr + wn * BM * E + row0 * E;
+  const float *own_base = s_own + row0 * E;
+  const int *tok_base = s_tok + row0 * E;
+  int *count_base = s_count + wn * BM * (E / 4) + row0 * (E / 4);
+  // staging: this thread's slots are (row = tid / E + 32 j, child = tid % E)
+  const int st_row = tid / E, st_e = tid % E;
+  for (int e0 = 0; e0 < max_cc; e0 += E) {
+    if (tid < BM) {
+      int n = my_cc - e0;
+      s_cc[tid] = n < 0 ? 0 : (n > E ? E : n);
+      s_pos[tid] = my_pos + e0;
+    }
+    __syncthreads();
+    {
+      // all threads stage the (row, child) slots of the pass: the loads of a thread's slots
+      // are in flight together, first the children's ids, then their tokens and own scores
+      constexpr int kSlots = BM * E / kGemmThreads, kRowStep = kGemmThreads / E, kChunk = 4;
+#pragma unroll
+      for (int j0 = 0; j0 < kSlots; j0 += kChunk) {
+        int c[kChunk], t[kChunk];
+        float o[kChunk];
+#pragma unroll
+        for (int j = 0; j < kChunk; ++j) {
+          const int row = st_row + kRowStep * (j0 + j);
+          c[j] = st_e < (s_cc[row] & 255) ? tb.child_list[s_pos[row] + st_e] : -1;
+        }
+#pragma unroll
+        for (int j = 0; j < kChunk; ++j) {
+          t[j] = c[j] >= 0 ? tb.token[c[j]] : -1;
+          o[j] = c[j] >= 0 ? tb.own[c[j]] : INFINITY;
+        }
+#pragma unroll
+        for (int j = 0; j < kChunk; ++j) {
+          const int row = st_row + kRowStep * (j0 + j), slot = row * E + st_e;
+          // an id outside the vocabulary is beaten by nothing here (the decision kernel fails it)
+          const bool ok = t[j] >= 0 && t[j] < vocab;
+          s_own[slot] = ok ? o[j] : INFINITY;
+          s_tok[slot] = ok ? t[j] : -1;
+          s_node[slot] = c[j];
+#pragma unroll
+          for (int half = 0; half < 2; ++half) {
+            const int c0 = v0 + half * WN;
+            float thr = INFINITY;
+            if (ok) {
+              const bool inside = t[j] >= c0 && t[j] < c0 + WN;
+              thr = t[j] < c0 ? o[j] : (inside ? __uint_as_float(0x7fc00000u) : float_pred(o[j]));
+              if (inside) atomicOr(&s_cc[row], 256 << half);  // this row has a side-path entry
+            }
+            s_thr[(half * BM * E) + slot] = thr;
+          }
+        }
+      }
+    }
+    __syncthreads();
+    // this lane's 32 rows, in the order (x, r); the thresholds of the next row are requested
+    // before the current row is counted
+    auto row_off = [](int idx) { return (idx >> 4) * 32 + 8 * ((idx & 15) >> 2) + (idx & 3); };
+    int meta_cur = cc_base[row_off(0)];  // children | side-path flags of the two wave columns << 8
+    f32x4 thr_cur = *reinterpret_cast<const f32x4 *>(thr_base + row_off(0) * E);
+    static_for<32>([&](auto idx_c) {
+      constexpr int idx = decltype(idx_c)::value;
+      constexpr int x = idx >> 4, r = idx & 15;
+      constexpr int off = (idx >> 4) * 32 + 8 * ((idx & 15) >> 2) + (idx & 3);
+      int meta_nxt = 0;
+      f32x4 thr_nxt = {0.f, 0.f, 0.f, 0.f};
+      if (idx + 1 < 32) {
+        meta_nxt = cc_base[row_off(idx + 1)];
+        thr_nxt = *reinterpret_cast<const f32x4 *>(thr_base + row_off(idx + 1) * E);
+      }
+      const int m_lo = __builtin_amdgcn_readlane(meta_cur, 0), m_hi = __builtin_amdgcn_readlane(meta_cur, 32);
+      const int n_both = (m_lo & 255) > (m_hi & 255) ? (m_lo & 255) : (m_hi & 255);
+      const bool side_path = (((m_lo | m_hi) >> (8 + wn)) & 1) != 0;  // rare: the token's own columns
+      for (int e4 = 0; e4 < n_both; e4 += 4) {
+        if (e4 > 0) thr_cur = *reinterpret_cast<const f32x4 *>(thr_base + off * E + e4);  // more than four children
+        int packed = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float thr = thr_cur[j];
+          int cnt = 0;
+#pragma unroll
+          for (int y = 0; y < FN; ++y) cnt += acc[x][y][r] > thr ? 1 : 0;
+          if (side_path && thr != thr) {
+            const float own = own_base[off * E + e4 + j];
+            const int tok = tok_base[off * E + e4 + j];
+#pragma unroll
+            for (int y = 0; y < FN; ++y) {
+              const int col = v0 + wn * WN + y * 32 + l32;
+              const float z = acc[x][y][r];
+              cnt += (z > own || (z == own && col < tok)) ? 1 : 0;
+            }
+          }
+          packed += cnt << (8 * j);
+        }
+        packed = half_wave_sum_to_last(packed);
+        if (l32 == 31) count_base[off * (E / 4) + (e4 >> 2)] = packed;
+      }
+      meta_cur = meta_nxt;
+      thr_cur = thr_nxt;
+    });
+    __syncthreads();
+    // every (child, column tile) slot is written by exactly one workgroup, zero counts too
+#pragma unroll
+    for (int j = 0; j < BM * E / kGemmThreads; ++j) {
+      const int row = st_row + (kGemmThreads / E) * j, slot = row * E + st_e;
+      const int c = s_node[slot];
+      if (c >= 0) {
+        const int word = slot >> 2, sh = 8 * (slot & 3);
+        tb.cnt_part[(size_t)n_tile * tb.cnt_stride + c] =
+            ((s_count[word] >> sh) & 255) + ((s_count[BM * (E / 4) + word] >> sh) & 255);
+      }
+    }
+    __syncthreads();  // the next pass, or the next tile's loads, reuse this memory
+  }
+}
+
+// (max, sum of exp(z - max)) of two parts of a row, merged
+__device__ __forceinline__ void lse_merge(float &m, float &s, float m2, float s2) {
+  const float mm = m > m2 ? m : m2;
+  s = (m == -INFINITY ? 0.f : s * expf(m - mm)) + (m2 == -INFINITY ? 0.f : s2 * expf(m2 - mm));
+  m = mm;
+}
+
+// Probability criterion: (max, sum of exponentials) of this wave's columns for every row of
+// the tile, one pair per row and column part, merged later by row_lse_kernel.
+template <int FN>
+__device__ __forceinline__ void epilogue_lse(const f32x16 (&acc)[2][FN], int m0, int v0, int m_total,
+                                             int vocab, int n_tile, int wm, int wn, int lane,
+                                             const HeadTables &tb) {
+  constexpr int WN = 32 * FN;
+  const int l32 = lane & 31, g = lane >> 5;
+#pragma unroll
+  for (int x = 0; x < 2; ++x)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      float mx = -INFINITY;
+#pragma unroll
+      for (int y = 0; y < FN; ++y)
+        if (v0 + wn * WN + y * 32 + l32 < vocab) mx = fmaxf(mx, acc[x][y][r]);
+#pragma unroll
+      for (int o = 16; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, kWave));
+      float sum = 0.f;
+#pragma unroll
+      for (int y = 0; y < FN; ++y)
+        if (v0 + wn * WN + y * 32 + l32 < vocab) sum += expf(acc[x][y][r] - mx);
+#pragma unroll
+      for (int o = 16; o > 0; o >>= 1) sum += __shfl_xor(sum, o, kWave);
+      const int m = m0 + wm * 64 + x * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+      if (l32 == 0 && m < m_total) {
+        float *dst = tb.lse_part + ((size_t)m * tb.parts + 2 * n_tile + wn) * 2;
+        dst[0] = mx;
+        dst[1] = sum;
+      }
+    }
+}
+
+template <int FN, int KIND>
 __device__ __forceinline__ void early_head_tile(
-    int hidden, int vocab, int m_total, int m0, int v0, const uint16_t *__restrict__ hidden_states,
-    const uint16_t *__restrict__ head_weight, const int32_t *__restrict__ row_src,
-    float *__restrict__ scores, size_t score_pitch, unsigned char *gemm_smem) {
-  constexpr int BM = kGemmBM, BN = 64 * FN, WN = 32 * FN;
+    int hidden, int vocab, int m_total, int m0, int v0, int n_tile,
+    const uint16_t *__restrict__ hidden_states, const uint16_t *__restrict__ head_weight,
+    const HeadTables &tb, unsigned char *gemm_smem) {
+  constexpr int BM = kGemmBM, WN = 32 * FN;
   constexpr int kStages = gemm_stages(FN), kStageBytes = gemm_stage_bytes(FN);
   typedef __attribute__((address_space(3))) void lds_void;
   typedef const __attribute__((address_space(1))) void global_void;
@@ -292,6 +727,12 @@ __device__ __forceinline__ void early_head_tile(
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
   const int l32 = lane & 31, g = lane >> 5;
+  // children of the tile's rows (thread t < 256 looks after row m0 + t), fetched early
+  int my_pos = 0, my_cc = 0;
+  if (KIND == 0 && tid < BM && m0 + tid < m_total) {
+    my_pos = tb.row_info[2 * (m0 + tid)];
+    my_cc = tb.row_info[2 * (m0 + tid) + 1];
+  }
 
   // ---- loader: a load instruction fills 16 rows (1 KB).  A stage has 16 such groups of A
   //      rows and 4*FN of W rows; wave w takes groups w and w+8 of each (the second W group
@@ -305,7 +746,7 @@ __device__ __forceinline__ void early_head_tile(
   for (int j = 0; j < 2; ++j) {
     int m = m0 + 16 * (wave + 8 * j) + ld_row;
     m = m < m_total ? m : m_total - 1;
-    a_src[j] = reinterpret_cast<const unsigned char *>(hidden_states + (size_t)row_src[m] * hidden) + ld_chunk;
+    a_src[j] = reinterpret_cast<const unsigned char *>(hidden_states + (size_t)tb.row_src[m] * hidden) + ld_chunk;
     int v = v0 + 16 * (wave + 8 * j) + ld_row;
     v = v < vocab ? v : vocab - 1;
     b_src[j] = reinterpret_cast<const unsigned char *>(head_weight + (size_t)v * hidden) + ld_chunk;
@@ -409,335 +850,254 @@ __device__ __forceinline__ void early_head_tile(
   mma(f1);
 
   mfma_settle();
-  // accumulator layout of the 32x32 MFMA: lane -> column l32, register r -> row
-  // 8*(r/4) + 4*g + r%4
-  const bool full = m0 + BM <= m_total && v0 + BN <= vocab;
-#pragma unroll
-  for (int x = 0; x < 2; ++x)
-#pragma unroll
-    for (int y = 0; y < FN; ++y) {
-      const int col = v0 + wn * WN + y * 32 + l32;
-      const int row0 = m0 + wm * 64 + x * 32 + 4 * g;
-      float *out = scores + (size_t)row0 * score_pitch + col;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int dr = 8 * (r >> 2) + (r & 3);
-        if (full || (row0 + dr < m_total && col < vocab)) out[(size_t)dr * score_pitch] = acc[x][y][r];
-      }
-    }
+  if (KIND == 0)
+    epilogue_count<FN>(acc, m0, v0, n_tile, vocab, tid, my_pos, my_cc, tb, gemm_smem);
+  else
+    epilogue_lse<FN>(acc, m0, v0, m_total, vocab, n_tile, wm, wn, lane, tb);
 }
 
+// Persistent over the tiles: tile -> (xcd, slot) as described above, a workgroup takes tiles
+// blockIdx.x, blockIdx.x + gridDim.x, ... (the grid is a multiple of the XCD count).
+template <int KIND>
 __global__ __launch_bounds__(kGemmThreads, 1) void early_head_bf16_kernel(
     int hidden, int vocab, int B, int cus, const uint16_t *__restrict__ hidden_states,
-    const uint16_t *__restrict__ head_weight, const int32_t *__restrict__ row_src,
-    const int32_t *__restrict__ row_base, float *__restrict__ scores, size_t score_pitch) {
-  const int m_total = row_base[B];
+    const uint16_t *__restrict__ head_weight, HeadTables tb) {
+  const int m_total = tb.row_base[B];
   const int m_tiles = (m_total + kGemmBM - 1) / kGemmBM;
   if (m_tiles == 0) return;
   const int fn = gemm_pick_fn(m_tiles, vocab, cus);
   const int n_tiles = (vocab + 64 * fn - 1) / (64 * fn);
-  const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
-  const int n_tile = (slot / m_tiles) * kXcds + xcd;
-  if (n_tile >= n_tiles) return;
-  const int m0 = (slot % m_tiles) * kGemmBM, v0 = n_tile * 64 * fn;
+  const long long total = (long long)kXcds * ((n_tiles + kXcds - 1) / kXcds) * m_tiles;
   extern __shared__ __attribute__((aligned(1024))) unsigned char gemm_smem[];
-  if (fn == 2)
-    early_head_tile<2>(hidden, vocab, m_total, m0, v0, hidden_states, head_weight, row_src, scores,
-                       score_pitch, gemm_smem);
-  else if (fn == 3)
-    early_head_tile<3>(hidden, vocab, m_total, m0, v0, hidden_states, head_weight, row_src, scores,
-                       score_pitch, gemm_smem);
-  else
-    early_head_tile<4>(hidden, vocab, m_total, m0, v0, hidden_states, head_weight, row_src, scores,
-                       score_pitch, gemm_smem);
+  for (long long tile = blockIdx.x; tile < total; tile += gridDim.x) {
+    const int xcd = (int)(tile % kXcds);
+    const long long slot = tile / kXcds;
+    const int n_tile = (int)(slot / m_tiles) * kXcds + xcd;
+    if (n_tile >= n_tiles) continue;
+    const int m0 = (int)(slot % m_tiles) * kGemmBM, v0 = n_tile * 64 * fn;
+    if (fn == 2)
+      early_head_tile<2, KIND>(hidden, vocab, m_total, m0, v0, n_tile, hidden_states, head_weight, tb, gemm_smem);
+    else if (fn == 3)
+      early_head_tile<3, KIND>(hidden, vocab, m_total, m0, v0, n_tile, hidden_states, head_weight, tb, gemm_smem);
+    else
+      early_head_tile<4, KIND>(hidden, vocab, m_total, m0, v0, n_tile, hidden_states, head_weight, tb, gemm_smem);
+  }
 }
 
-// fp32 variant: one score per thread, a plain sequential dot product.
+// fp32 variant: one score per thread, a plain sequential dot product, then the same two
+// epilogues on a 256-wide slice of the row (column part = slice index).
+template <int KIND>
 __global__ __launch_bounds__(256) void early_head_f32_kernel(
     int hidden, int vocab, int B, const float *__restrict__ hidden_states,
-    const float *__restrict__ head_weight, const int32_t *__restrict__ row_src,
-    const int32_t *__restrict__ row_base, float *__restrict__ scores, size_t score_pitch) {
+    const float *__restrict__ head_weight, HeadTables tb) {
   const int m = blockIdx.x;
-  if (m >= row_base[B]) return;
+  if (m >= tb.row_base[B]) return;
   const int v = blockIdx.y * 256 + threadIdx.x;
-  if (v >= vocab) return;
-  const float *h = hidden_states + (size_t)row_src[m] * hidden;
-  const float *w = head_weight + (size_t)v * hidden;
-  float acc = 0.f;
-  for (int x = 0; x < hidden; ++x) acc = fmaf(h[x], w[x], acc);
-  scores[(size_t)m * score_pitch + v] = acc;
-}
-
-// ------------------------------------------------------------------------------------
-// top-k membership by counting
-// ------------------------------------------------------------------------------------
-constexpr int kRankThreads = 256;
-constexpr int kRankChunk = 8;     // children compared per pass over the scores
-constexpr int kRankSplit = 4;     // workgroups sharing one parent row (column slices)
-
-// One pass over a slice of a score row for NC children at once: counts, per child, the scores
-// that beat its token's (a higher score, or the same score at a lower id), adds the counts of
-// the workgroup up in LDS and then onto the children's ranks.
-template <int NC>
-__device__ __forceinline__ void rank_pass(int b, int T_max, int vocab, int c0, int nchild, int part,
-                                          int c_lo, int c_hi, int nvec, const float *__restrict__ z,
-                                          const int32_t *__restrict__ token, const int *s_child,
-                                          int *s_count, int32_t *__restrict__ rank) {
-  const int tid = threadIdx.x;
-  float thr[NC];
-  int tok[NC], cnt[NC];
-#pragma unroll
-  for (int e = 0; e < NC; ++e) {
-    thr[e] = INFINITY;  // unused slot: nothing beats +inf, nothing ties below id -1
-    tok[e] = -1;
-    cnt[e] = 0;
-    if (c0 + e < nchild) {
-      const int t = token[(size_t)b * T_max + s_child[c0 + e]];
-      if (t >= 0 && t < vocab) {
-        thr[e] = z[t];
-        tok[e] = t;
-      }
+  const bool in = v < vocab;
+  const float *h = hidden_states + (size_t)tb.row_src[m] * hidden;
+  const float *w = head_weight + (size_t)(in ? v : vocab - 1) * hidden;
+  float z = 0.f;
+  for (int x = 0; x < hidden; ++x) z = fmaf(h[x], w[x], z);
+  const int lane = threadIdx.x & 63;
+  if (KIND == 0) {
+    __shared__ int s_cnt[4];
+    const int pos = tb.row_info[2 * m], cc = tb.row_info[2 * m + 1];
+    for (int e = 0; e < cc; ++e) {
+      const int c = tb.child_list[pos + e];
+      const int t = tb.token[c];
+      const bool ok = t >= 0 && t < vocab;  // an id outside the vocabulary: the decision kernel fails it
+      const float own = tb.own[c];
+      const int cnt = __popcll(__ballot(ok && in && (z > own || (z == own && v < t))));
+      if (lane == 0) s_cnt[threadIdx.x >> 6] = cnt;
+      __syncthreads();
+      if (threadIdx.x == 0)
+        tb.cnt_part[(size_t)blockIdx.y * tb.cnt_stride + c] = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
+      __syncthreads();
     }
-  }
-  if (tid < NC) s_count[tid] = 0;
-  __syncthreads();
-  // four loads of a lane in flight before the first is used (a position past the slice
-  // re-reads the slice's first vector and is not counted)
-  constexpr int kInFlight = 4;
-  for (int c0 = c_lo + tid; c0 < c_hi; c0 += kInFlight * kRankThreads) {
-    f32x4 u[kInFlight];
-#pragma unroll
-    for (int k = 0; k < kInFlight; ++k) {
-      const int c = c0 + k * kRankThreads;
-      u[k] = *reinterpret_cast<const f32x4 *>(z + 4 * (c < c_hi ? c : c_lo));
+  } else {
+    float mx = in ? z : -INFINITY;
+    mx = wave_reduce_max(mx);
+    float sum = in ? expf(z - mx) : 0.f;
+    sum = wave_reduce_sum(sum);
+    __shared__ float s_m[4], s_s[4];
+    if (lane == 0) {
+      s_m[threadIdx.x >> 6] = mx;
+      s_s[threadIdx.x >> 6] = sum;
     }
-#pragma unroll
-    for (int k = 0; k < kInFlight; ++k) {
-      const int c = c0 + k * kRankThreads;
-      if (c >= c_hi) break;
-      const int v = 4 * c;
-#pragma unroll
-      for (int e = 0; e < NC; ++e) {
-        cnt[e] += (u[k].x > thr[e]) || (u[k].x == thr[e] && v < tok[e]);
-        cnt[e] += (u[k].y > thr[e]) || (u[k].y == thr[e] && v + 1 < tok[e]);
-        cnt[e] += (u[k].z > thr[e]) || (u[k].z == thr[e] && v + 2 < tok[e]);
-        cnt[e] += (u[k].w > thr[e]) || (u[k].w == thr[e] && v + 3 < tok[e]);
-      }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      for (int wv = 1; wv < 4; ++wv) lse_merge(mx, sum, s_m[wv], s_s[wv]);
+      float *dst = tb.lse_part + ((size_t)m * tb.parts + blockIdx.y) * 2;
+      dst[0] = mx;
+      dst[1] = sum;
     }
-  }
-  if (part == kRankSplit - 1)
-    for (int v = 4 * nvec + tid; v < vocab; v += kRankThreads) {
-      const float x = z[v];
-#pragma unroll
-      for (int e = 0; e < NC; ++e) cnt[e] += (x > thr[e]) || (x == thr[e] && v < tok[e]);
-    }
-#pragma unroll
-  for (int e = 0; e < NC; ++e) {
-    const int sum = wave_reduce_sum(cnt[e]);
-    if ((tid & 63) == 0 && sum) atomicAdd(&s_count[e], sum);
-  }
-  __syncthreads();
-  if (tid < NC && c0 + tid < nchild) {
-    int mine = 0;
-    bool valid_tok = false;
-#pragma unroll
-    for (int e = 0; e < NC; ++e)
-      if (e == tid) {
-        mine = s_count[e];
-        valid_tok = tok[e] >= 0;
-      }
-    int32_t *dst = &rank[(size_t)b * T_max + s_child[c0 + tid]];
-    // a token id outside the vocabulary can be in no top-k list
-    if (!valid_tok) {
-      if (part == 0) atomicAdd(dst, vocab);
-    } else if (mine) {
-      atomicAdd(dst, mine);
-    }
-  }
-  __syncthreads();
-}
-
-// One parent row is shared by kRankSplit workgroups, each counting over its own slice of
-// the vocabulary and adding its counts to the children's ranks with integer atomics (the
-// sum does not depend on the order).  ranks of children were zeroed by parent_rows_kernel.
-// Children are taken up to kRankChunk at a time, in a pass specialised for 1, 2, 4 or 8 of
-// them: most nodes have one or two children and the compare work goes with that number.
-__global__ __launch_bounds__(kRankThreads) void rank_count_kernel(
-    int B, int T_max, int vocab, const int32_t *__restrict__ n_nodes,
-    const int32_t *__restrict__ parent, const int32_t *__restrict__ token,
-    const int32_t *__restrict__ row_src, const int32_t *__restrict__ row_base,
-    const float *__restrict__ scores, size_t score_pitch, int32_t *__restrict__ rank) {
-  const int m = blockIdx.x / kRankSplit, part = blockIdx.x - m * kRankSplit;
-  if (m >= row_base[B]) return;
-  const int node = row_src[m];
-  const int b = node / T_max, p = node - b * T_max;
-  int T = n_nodes[b];
-  T = T < 1 ? 1 : (T > T_max ? T_max : T);
-  const int tid = threadIdx.x;
-  __shared__ int s_child[PROPD_MAX_TREE];
-  __shared__ int s_nchild;
-  __shared__ int s_count[kRankChunk];
-  if (tid == 0) s_nchild = 0;
-  __syncthreads();
-  if (tid > p && tid < T && parent[(size_t)b * T_max + tid] == p)
-    s_child[atomicAdd(&s_nchild, 1)] = tid;
-  __syncthreads();
-  const int nchild = s_nchild;
-  const float *z = scores + (size_t)m * score_pitch;
-  // this workgroup's slice, in units of 4 scores; the last slice also takes the tail
-  const int nvec = vocab >> 2;
-  const int per = (nvec + kRankSplit - 1) / kRankSplit;
-  const int c_lo = part * per, c_hi = (c_lo + per < nvec) ? c_lo + per : nvec;
-
-  for (int c0 = 0; c0 < nchild; c0 += kRankChunk) {
-    const int here = nchild - c0;
-    if (here <= 1)
-      rank_pass<1>(b, T_max, vocab, c0, nchild, part, c_lo, c_hi, nvec, z, token, s_child, s_count, rank);
-    else if (here <= 2)
-      rank_pass<2>(b, T_max, vocab, c0, nchild, part, c_lo, c_hi, nvec, z, token, s_child, s_count, rank);
-    else if (here <= 4)
-      rank_pass<4>(b, T_max, vocab, c0, nchild, part, c_lo, c_hi, nvec, z, token, s_child, s_count, rank);
-    else
-      rank_pass<kRankChunk>(b, T_max, vocab, c0, nchild, part, c_lo, c_hi, nvec, z, token, s_child, s_count, rank);
   }
 }
 
 // ------------------------------------------------------------------------------------
 // probability-based selection (Section 4.1, "Pruning Criterion", second criterion)
 // ------------------------------------------------------------------------------------
-constexpr int kLseThreads = 256;
-
-// (max, sum of exp(x - max)) of two parts of a row, merged
-__device__ __forceinline__ void lse_merge(float &m, float &s, float m2, float s2) {
-  const float mm = m > m2 ? m : m2;
-  s = (m == -INFINITY ? 0.f : s * expf(m - mm)) + (m2 == -INFINITY ? 0.f : s2 * expf(m2 - mm));
-  m = mm;
-}
-
-// One workgroup per parent row: one pass over the row's scores for log sum_v exp(z[v]), then
-// logq = z[token] - that for every child of the row's node.  A token id outside the
-// vocabulary has probability 0 (logq = -inf).
-__global__ __launch_bounds__(kLseThreads) void child_logprob_kernel(
-    int B, int T_max, int vocab, const int32_t *__restrict__ n_nodes,
-    const int32_t *__restrict__ parent, const int32_t *__restrict__ token,
-    const int32_t *__restrict__ row_src, const int32_t *__restrict__ row_base,
-    const float *__restrict__ scores, size_t score_pitch, float *__restrict__ logq) {
+// One wave per score row: log sum_v exp(z[v]) from the row's tile partials (the first
+// n_parts of them were written), then logq = own score - that for every child of the
+// row's node.  A token id outside the vocabulary has probability 0 (logq = -inf).
+__global__ __launch_bounds__(kWave) void row_lse_kernel(int B, int vocab, int cus, int bf16,
+                                                        HeadTables tb, float *__restrict__ logq) {
   const int m = blockIdx.x;
-  if (m >= row_base[B]) return;
-  const int node = row_src[m];
-  const int b = node / T_max, p = node - b * T_max;
-  int T = n_nodes[b];
-  T = T < 1 ? 1 : (T > T_max ? T_max : T);
-  const int tid = threadIdx.x;
-  const float *z = scores + (size_t)m * score_pitch;
-  float mx = -INFINITY, sum = 0.f;
-  const int nvec = vocab >> 2;
-  for (int c = tid; c < nvec; c += kLseThreads) {
-    const f32x4 u = *reinterpret_cast<const f32x4 *>(z + 4 * c);
-    const float m4 = fmaxf(fmaxf(u.x, u.y), fmaxf(u.z, u.w));
-    const float s4 = expf(u.x - m4) + expf(u.y - m4) + expf(u.z - m4) + expf(u.w - m4);
-    lse_merge(mx, sum, m4, s4);
+  const int m_total = tb.row_base[B];
+  if (m >= m_total) return;
+  int n_parts;
+  if (bf16) {
+    const int fn = gemm_pick_fn((m_total + kGemmBM - 1) / kGemmBM, vocab, cus);
+    n_parts = 2 * ((vocab + 64 * fn - 1) / (64 * fn));
+  } else {
+    n_parts = (vocab + 255) / 256;
   }
-  for (int v = 4 * nvec + tid; v < vocab; v += kLseThreads) lse_merge(mx, sum, z[v], 1.f);
+  const int lane = threadIdx.x;
+  float mx = -INFINITY, sum = 0.f;
+  const float *part = tb.lse_part + (size_t)m * tb.parts * 2;
+  for (int i = lane; i < n_parts; i += kWave) lse_merge(mx, sum, part[2 * i], part[2 * i + 1]);
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
     const float m2 = __shfl_xor(mx, o, kWave), s2 = __shfl_xor(sum, o, kWave);
     lse_merge(mx, sum, m2, s2);
   }
-  __shared__ float s_m[kLseThreads / kWave], s_s[kLseThreads / kWave];
-  if ((tid & 63) == 0) {
-    s_m[tid >> 6] = mx;
-    s_s[tid >> 6] = sum;
-  }
-  __syncthreads();
-  mx = s_m[0];
-  sum = s_s[0];
-#pragma unroll
-  for (int w = 1; w < kLseThreads / kWave; ++w) lse_merge(mx, sum, s_m[w], s_s[w]);
   const float lse = mx + logf(sum);
-  if (tid > p && tid < T && parent[(size_t)b * T_max + tid] == p) {
-    const int t = token[(size_t)b * T_max + tid];
-    logq[(size_t)b * T_max + tid] = (t >= 0 && t < vocab) ? z[t] - lse : -INFINITY;
+  const int pos = tb.row_info[2 * m], cc = tb.row_info[2 * m + 1];
+  for (int e = lane; e < cc; e += kWave) {
+    const int c = tb.child_list[pos + e];
+    const int t = tb.token[c];
+    logq[c] = (t >= 0 && t < vocab) ? tb.own[c] - lse : -INFINITY;
   }
 }
 
-// One workgroup per sequence, one lane per node: the log marginal of a node's sequence is the
-// sum of logq over its root path (the cached ancestor set, root excluded, in root-to-node
-// order); then the test.  mode 0: pruned when the marginal is below the threshold; mode 1:
-// pruned when `keep_count` or more sequences of the tree are more probable (equal marginals:
-// the lower node index counts as more probable).  A marginal of zero probability is always
-// pruned.  The result is written as a 0/1 "rank" for prune_compact_kernel with k = 1.
-__global__ __launch_bounds__(PROPD_MAX_TREE) void prob_decide_kernel(
-    int T_max, int mode, float log_threshold, int keep_count, const int32_t *__restrict__ n_nodes,
-    const uint64_t *__restrict__ anc, const float *__restrict__ logq, int32_t *__restrict__ rank,
-    float *__restrict__ log_marginal) {
-  const int b = blockIdx.x, i = threadIdx.x;
-  int T = n_nodes[b];
-  T = T < 1 ? 1 : (T > T_max ? T_max : T);
-  const size_t base = (size_t)b * T_max;
-  const bool valid = i < T;
-  __shared__ float s_q[PROPD_MAX_TREE], s_lm[PROPD_MAX_TREE];
-  s_q[i] = (valid && i > 0) ? logq[base + i] : 0.f;
-  __syncthreads();
-  float lm = 0.f;
-  if (valid && i > 0) {
-    uint64_t lo = anc[(base + i) * 2] & ~1ull, hi = anc[(base + i) * 2 + 1];
-    while (lo) {
-      lm += s_q[__ffsll((long long)lo) - 1];
-      lo &= lo - 1;
-    }
-    while (hi) {
-      lm += s_q[64 + __ffsll((long long)hi) - 1];
-      hi &= hi - 1;
-    }
-  }
-  s_lm[i] = valid ? lm : -INFINITY;
-  __syncthreads();
-  bool fail = false;
-  if (valid && i > 0) {
-    if (mode == 0) {
-      fail = !(lm >= log_threshold);
-    } else {
-      int ahead = 0;
-      for (int j = 0; j < T; ++j) ahead += (s_lm[j] > lm) || (s_lm[j] == lm && j < i);
-      fail = ahead >= keep_count;
-    }
-    fail = fail || !(lm > -INFINITY);
-  }
-  if (i < T_max) {
-    rank[base + i] = valid ? (fail ? 1 : 0) : -1;
-    if (log_marginal) log_marginal[base + i] = valid ? lm : 0.f;
-  }
-}
+// which criterion decides (Section 4.1, "Pruning Criterion")
+struct Criterion {
+  int kind;             // 0 top-k, 1 probability threshold, 2 probability rank
+  int top_k;            // kind 0
+  float log_threshold;  // kind 1
+  int keep_count;       // kind 2
+  float *log_marginal;  // kinds 1, 2: optional output
+};
 
 // ------------------------------------------------------------------------------------
-// branch elimination, compaction, mask subsampling
+// the decision, branch elimination, compaction, mask subsampling
 // ------------------------------------------------------------------------------------
-__global__ __launch_bounds__(PROPD_MAX_TREE) void prune_compact_kernel(
-    int T_max, int top_k, const int32_t *__restrict__ n_nodes, const int32_t *__restrict__ parent,
-    const int32_t *__restrict__ token, const int32_t *__restrict__ depth,
-    const uint64_t *__restrict__ anc, const int32_t *__restrict__ rank,
-    uint64_t *__restrict__ keep_bits, int32_t *__restrict__ new_index,
-    int32_t *__restrict__ orig_index, int32_t *__restrict__ n_kept,
+// One workgroup per sequence, one lane per node.
+//   top-k: a node fails when `top_k` or more scores of its parent's row beat its token's, or
+//     its token id lies outside the vocabulary.
+//   probability: the log marginal of a node's sequence is the sum of logq over its root path
+//     (the cached ancestor set, root excluded, in root-to-node order); it fails when the
+//     marginal is below the threshold, or when `keep_count` or more sequences of the tree are
+//     more probable (equal marginals: the lower node index counts as more probable); a
+//     marginal of zero probability always fails.
+constexpr int kCompactSplit = 4;  // threads that add up one node's per-tile counts
+
+__global__ __launch_bounds__(PROPD_MAX_TREE * kCompactSplit) void prune_compact_kernel(
+    int B, int T_max, int vocab, int cus, int bf16, Criterion crit, const int32_t *__restrict__ n_nodes,
+    const int32_t *__restrict__ parent, const int32_t *__restrict__ token,
+    const int32_t *__restrict__ depth, const uint64_t *__restrict__ anc,
+    const int32_t *__restrict__ row_base, const int32_t *__restrict__ cnt_part,
+    const float *__restrict__ logq, uint64_t *__restrict__ keep_bits,
+    int32_t *__restrict__ new_index, int32_t *__restrict__ orig_index, int32_t *__restrict__ n_kept,
     int32_t *__restrict__ out_n_nodes, int32_t *__restrict__ out_parent,
     int32_t *__restrict__ out_token, int32_t *__restrict__ out_depth,
     uint64_t *__restrict__ out_anc, int32_t *__restrict__ rank_out) {
-  const int b = blockIdx.x, i = threadIdx.x;
-  int T = n_nodes[b];
-  T = T < 1 ? 1 : (T > T_max ? T_max : T);
+  const int b = blockIdx.x, i = threadIdx.x & (PROPD_MAX_TREE - 1), q = threadIdx.x / PROPD_MAX_TREE;
+  const int T = clamp_tree(n_nodes[b], T_max);
   const size_t base = (size_t)b * T_max;
   const bool valid = i < T;
   __shared__ uint64_t s_fail[2], s_keep[2];
+  __shared__ float s_q[PROPD_MAX_TREE], s_lm[PROPD_MAX_TREE];
+  __shared__ int s_sum[kCompactSplit][PROPD_MAX_TREE];
 
-  int my_rank = -1;
+  if (crit.kind == 0) {
+    // rank = the counts of all column tiles (row_base == NULL: nothing was scored)
+    int n_tiles = 0;
+    if (row_base) {
+      const int m_total = row_base[B];
+      if (bf16) {
+        const int m_tiles = (m_total + kGemmBM - 1) / kGemmBM;
+        if (m_tiles > 0) n_tiles = (vocab + 64 * gemm_pick_fn(m_tiles, vocab, cus) - 1) / (64 * gemm_pick_fn(m_tiles, vocab, cus));
+      } else if (m_total > 0) {
+        n_tiles = (vocab + 255) / 256;
+      }
+    }
+    int sum = 0;
+    if (valid && i > 0) {
+      const int32_t *src = cnt_part + base + i;
+      const size_t stride = (size_t)B * T_max;
+      constexpr int kInFlight = 8;
+      for (int t0 = q; t0 < n_tiles; t0 += kCompactSplit * kInFlight) {
+        int v[kInFlight];
+#pragma unroll
+        for (int k = 0; k < kInFlight; ++k) {
+          const int t = t0 + kCompactSplit * k;
+          v[k] = t < n_tiles ? src[(size_t)t * stride] : 0;
+        }
+#pragma unroll
+        for (int k = 0; k < kInFlight; ++k) sum += v[k];
+      }
+    }
+    s_sum[q][i] = sum;
+  }
+  __syncthreads();
+  // from here on one thread per node does the work; the others only meet it at the barriers
+  const bool worker = q == 0;
   uint64_t a_lo = 0, a_hi = 0;
-  if (valid) {
-    my_rank = rank[base + i];
+  int my_token = -1;
+  if (worker && valid) {
     a_lo = anc[(base + i) * 2];
     a_hi = anc[(base + i) * 2 + 1];
+    my_token = token[base + i];
   }
-  if (rank_out && i < T_max) rank_out[base + i] = my_rank;
-  const bool fail = valid && i > 0 && my_rank >= top_k;
+  bool fail = false;
+  if (crit.kind == 0) {
+    if (worker) {
+      int my_rank = -1;
+      if (valid) {
+        my_rank = 0;
+#pragma unroll
+        for (int k = 0; k < kCompactSplit; ++k) my_rank += s_sum[k][i];
+        // a token id outside the vocabulary can be in no top-k list
+        if (i > 0 && (my_token < 0 || my_token >= vocab)) my_rank = vocab;
+      }
+      if (rank_out && i < T_max) rank_out[base + i] = my_rank;
+      fail = valid && i > 0 && my_rank >= crit.top_k;
+    }
+  } else {
+    if (worker) s_q[i] = (valid && i > 0) ? logq[base + i] : 0.f;
+    __syncthreads();
+    float lm = 0.f;
+    if (worker && valid && i > 0) {
+      uint64_t lo = a_lo & ~1ull, hi = a_hi;
+      while (lo) {
+        lm += s_q[__ffsll((long long)lo) - 1];
+        lo &= lo - 1;
+      }
+      while (hi) {
+        lm += s_q[64 + __ffsll((long long)hi) - 1];
+        hi &= hi - 1;
+      }
+    }
+    if (worker) s_lm[i] = valid ? lm : -INFINITY;
+    __syncthreads();
+    if (worker && valid && i > 0) {
+      if (crit.kind == 1) {
+        fail = !(lm >= crit.log_threshold);
+      } else {
+        int ahead = 0;
+        for (int j = 0; j < T; ++j) ahead += (s_lm[j] > lm) || (s_lm[j] == lm && j < i);
+        fail = ahead >= crit.keep_count;
+      }
+      fail = fail || !(lm > -INFINITY);
+    }
+    if (worker && crit.log_marginal && i < T_max) crit.log_marginal[base + i] = valid ? lm : 0.f;
+  }
+  if (!worker) {  // the two barriers below
+    __syncthreads();
+    __syncthreads();
+    return;
+  }
   const uint64_t fb = __ballot(fail);
   if ((i & 63) == 0) s_fail[i >> 6] = fb;
   __syncthreads();
@@ -752,7 +1112,7 @@ __global__ __launch_bounds__(PROPD_MAX_TREE) void prune_compact_kernel(
   if (i < T_max) new_index[base + i] = ni;
   if (keep) {
     orig_index[base + ni] = i;
-    out_token[base + ni] = token[base + i];
+    out_token[base + ni] = my_token;
     out_depth[base + ni] = depth[base + i];
     int p = i == 0 ? -1 : parent[base + i];
     out_parent[base + ni] = (p >= 0 && p < T) ? popc128_below(k_lo, k_hi, p) : -1;
@@ -885,14 +1245,6 @@ __global__ __launch_bounds__(kGatherThreads) void gather_rows_kernel(
   }
 }
 
-__global__ void fill_rank_kernel(int n, int T_max, const int32_t *__restrict__ n_nodes,
-                                 int32_t *__restrict__ rank) {
-  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= n) return;
-  const int b = idx / T_max, i = idx - b * T_max;
-  rank[idx] = i < n_nodes[b] ? 0 : -1;
-}
-
 }  // namespace propd
 
 static int prune_compute_units() {
@@ -907,27 +1259,15 @@ static int prune_compute_units() {
   return cus;
 }
 
-namespace {
-// which criterion decides (Section 4.1, "Pruning Criterion")
-struct Criterion {
-  int kind;             // 0 top-k, 1 probability threshold, 2 probability rank
-  int top_k;            // kind 0
-  float log_threshold;  // kind 1
-  int keep_count;       // kind 2
-  float *log_marginal;  // kinds 1, 2: optional output
-};
-}  // namespace
-
 static propd_status prune_impl(
-    const Criterion &crit, const propd_tree *tree, propd_dtype dt, int32_t hidden, int32_t vocab,
+    const propd::Criterion &crit, const propd_tree *tree, propd_dtype dt, int32_t hidden, int32_t vocab,
     const void *hidden_states, const void *head_weight, uint64_t *keep_bits, int32_t *new_index,
     int32_t *orig_index, int32_t *n_kept, int32_t *cu_nodes, const propd_tree_out *tree_out,
     int32_t *rank_out, int32_t n_payloads, const propd_payload *payloads, void *workspace,
     size_t workspace_bytes, void *hip_stream) {
   using namespace propd;
-  const int top_k = crit.kind == 0 ? crit.top_k : 1;  // the 0/1 flags of the other kinds pass below 1
   if (!tree || tree->B < 1 || tree->T_max < 1 || tree->T_max > PROPD_MAX_TREE || hidden < 1 ||
-      vocab < 1 || top_k < 1)
+      vocab < 1 || (crit.kind == 0 && crit.top_k < 1))
     return PROPD_ERR_INVALID_ARG;
   if (!tree->n_nodes || !tree->parent || !tree->token || !tree->depth || !tree->anc ||
       !hidden_states || !head_weight || !keep_bits || !new_index || !orig_index || !n_kept ||
@@ -938,8 +1278,14 @@ static propd_status prune_impl(
   if (n_payloads < 0 || n_payloads > PROPD_MAX_PAYLOADS || (n_payloads > 0 && !payloads))
     return PROPD_ERR_INVALID_ARG;
   if (dt == PROPD_BF16 && hidden % kBK != 0) return PROPD_ERR_UNSUPPORTED;
+  // operand rows are fetched 16 bytes per lane (bf16) or 4 (fp32); the scratch holds 8-byte records
+  const uintptr_t op_align = dt == PROPD_BF16 ? 16 : 4;
+  if (reinterpret_cast<uintptr_t>(hidden_states) % op_align != 0 ||
+      reinterpret_cast<uintptr_t>(head_weight) % op_align != 0 ||
+      reinterpret_cast<uintptr_t>(workspace) % 16 != 0 || reinterpret_cast<uintptr_t>(tree->anc) % 8 != 0)
+    return PROPD_ERR_INVALID_ARG;
   const int B = tree->B, T_max = tree->T_max;
-  if ((long long)B * T_max > (1ll << 27)) return PROPD_ERR_UNSUPPORTED;
+  if ((long long)B * T_max > (1ll << 24)) return PROPD_ERR_UNSUPPORTED;
   long long max_rows = 0, total_blocks = 0;
   PayloadArgs pa = {};
   for (int p = 0; p < n_payloads; ++p) {
@@ -975,59 +1321,92 @@ static propd_status prune_impl(
   PruneScratch ws = carve_scratch(workspace, B, T_max, vocab);
   hipStream_t st = as_stream(hip_stream);
 
-  if (crit.kind == 0 && top_k >= vocab) {
-    // every id is inside the list: nothing can fail, no scores are needed
-    const int n = B * T_max;
-    hipLaunchKernelGGL(fill_rank_kernel, dim3((n + 255) / 256), dim3(256), 0, st, n, T_max,
-                       tree->n_nodes, ws.rank);
-  } else {
-    hipLaunchKernelGGL(parent_rows_kernel, dim3(B), dim3(PROPD_MAX_TREE), 0, st, T_max,
-                       tree->n_nodes, tree->parent, ws.n_par, ws.local_list, ws.rank);
-    hipLaunchKernelGGL(row_table_kernel, dim3((unsigned)((B * T_max + kScanThreads - 1) / kScanThreads)),
-                       dim3(kScanThreads), 0, st, B, T_max, ws.n_par,
-                       ws.local_list, ws.row_base, ws.row_src);
+  const bool scored = !(crit.kind == 0 && crit.top_k >= vocab);
+  // top_k >= vocab: every id of the vocabulary is inside the list, no scores are needed (ids
+  // outside the vocabulary still fail, in the decision kernel)
+  const int cus = prune_compute_units();
+  if (scored) {
+    PrepareArgs pr;
+    pr.B = B;
+    pr.T_max = T_max;
+    pr.hidden = hidden;
+    pr.vocab = vocab;
+    pr.n_nodes = tree->n_nodes;
+    pr.parent = tree->parent;
+    pr.token = tree->token;
+    pr.hidden_states = hidden_states;
+    pr.head_weight = head_weight;
+    pr.n_par = ws.n_par;
+    pr.local_list = ws.local_list;
+    pr.row_src = ws.row_src;
+    pr.row_base = ws.row_base;
+    pr.row_info = ws.row_info;
+    pr.child_pos = ws.child_pos;
+    pr.child_cnt = ws.child_cnt;
+    pr.child_list = ws.child_list;
+    pr.own = ws.own;
+    const unsigned prep_grid = 1u + (unsigned)B * (unsigned)((T_max + kOwnNodes - 1) / kOwnNodes);
+    if (dt == PROPD_BF16)
+      hipLaunchKernelGGL(prune_prepare_kernel<true>, dim3(prep_grid), dim3(kScanThreads), 0, st, pr);
+    else
+      hipLaunchKernelGGL(prune_prepare_kernel<false>, dim3(prep_grid), dim3(kScanThreads), 0, st, pr);
+    if (!launch_ok()) return PROPD_ERR_DEVICE;
+    HeadTables tb;
+    tb.row_src = ws.row_src;
+    tb.row_base = ws.row_base;
+    tb.row_info = ws.row_info;
+    tb.child_list = ws.child_list;
+    tb.token = tree->token;
+    tb.own = ws.own;
+    tb.cnt_part = ws.cnt_part;
+    tb.cnt_stride = B * T_max;
+    tb.lse_part = ws.lse_part;
+    tb.parts = (int)ws.parts;
     if (dt == PROPD_BF16) {
-      constexpr int BM = kGemmBM, BN = 64 * kGemmMinFN;  // the grid covers the narrowest tiles
+      constexpr int BM = kGemmBM, BN = 64 * kGemmMinFN;  // the tile count is largest for the narrowest tiles
       static bool attr_set = false;
       if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&early_head_bf16_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize,
-                                kGemmLdsBytes) != hipSuccess)
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&early_head_bf16_kernel<0>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void *>(&early_head_bf16_kernel<1>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes) != hipSuccess)
           return PROPD_ERR_DEVICE;
         attr_set = true;
       }
+      // one workgroup per compute unit and round, two rounds resident in the queue; fewer when
+      // even the largest row count has fewer tiles
       const long long m_tiles_cap = (ws.row_cap + BM - 1) / BM;
       const long long n_groups = ((vocab + BN - 1) / BN + kXcds - 1) / kXcds;
-      const long long grid = kXcds * n_groups * m_tiles_cap;
-      if (grid > (1ll << 31) - 1) return PROPD_ERR_UNSUPPORTED;
-      hipLaunchKernelGGL(early_head_bf16_kernel, dim3((unsigned)grid), dim3(kGemmThreads),
-                         kGemmLdsBytes, st, hidden, vocab, B, prune_compute_units(),
-                         reinterpret_cast<const uint16_t *>(hidden_states),
-                         reinterpret_cast<const uint16_t *>(head_weight), ws.row_src, ws.row_base,
-                         ws.scores, ws.score_pitch);
+      long long grid = kXcds * n_groups * m_tiles_cap;
+      const long long persistent = (2ll * cus + kXcds - 1) / kXcds * kXcds;
+      grid = grid < persistent ? grid : persistent;
+      if (crit.kind == 0)
+        hipLaunchKernelGGL(early_head_bf16_kernel<0>, dim3((unsigned)grid), dim3(kGemmThreads), kGemmLdsBytes, st,
+                           hidden, vocab, B, cus, reinterpret_cast<const uint16_t *>(hidden_states),
+                           reinterpret_cast<const uint16_t *>(head_weight), tb);
+      else
+        hipLaunchKernelGGL(early_head_bf16_kernel<1>, dim3((unsigned)grid), dim3(kGemmThreads), kGemmLdsBytes, st,
+                           hidden, vocab, B, cus, reinterpret_cast<const uint16_t *>(hidden_states),
+                           reinterpret_cast<const uint16_t *>(head_weight), tb);
     } else {
       dim3 grid((unsigned)ws.row_cap, (unsigned)((vocab + 255) / 256));
-      hipLaunchKernelGGL(early_head_f32_kernel, grid, dim3(256), 0, st, hidden, vocab, B,
-                         reinterpret_cast<const float *>(hidden_states),
-                         reinterpret_cast<const float *>(head_weight), ws.row_src, ws.row_base,
-                         ws.scores, ws.score_pitch);
+      if (crit.kind == 0)
+        hipLaunchKernelGGL(early_head_f32_kernel<0>, grid, dim3(256), 0, st, hidden, vocab, B,
+                           reinterpret_cast<const float *>(hidden_states),
+                           reinterpret_cast<const float *>(head_weight), tb);
+      else
+        hipLaunchKernelGGL(early_head_f32_kernel<1>, grid, dim3(256), 0, st, hidden, vocab, B,
+                           reinterpret_cast<const float *>(hidden_states),
+                           reinterpret_cast<const float *>(head_weight), tb);
     }
-    if (crit.kind == 0) {
-      hipLaunchKernelGGL(rank_count_kernel, dim3((unsigned)(ws.row_cap * kRankSplit)), dim3(kRankThreads), 0, st, B,
-                         T_max, vocab, tree->n_nodes, tree->parent, tree->token, ws.row_src,
-                         ws.row_base, ws.scores, ws.score_pitch, ws.rank);
-    } else {
-      hipLaunchKernelGGL(child_logprob_kernel, dim3((unsigned)ws.row_cap), dim3(kLseThreads), 0, st, B,
-                         T_max, vocab, tree->n_nodes, tree->parent, tree->token, ws.row_src,
-                         ws.row_base, ws.scores, ws.score_pitch, ws.logq);
-      hipLaunchKernelGGL(prob_decide_kernel, dim3(B), dim3(PROPD_MAX_TREE), 0, st, T_max,
-                         crit.kind == 1 ? 0 : 1, crit.log_threshold, crit.keep_count, tree->n_nodes,
-                         tree->anc, ws.logq, ws.rank, crit.log_marginal);
-    }
+    if (crit.kind != 0)
+      hipLaunchKernelGGL(row_lse_kernel, dim3((unsigned)ws.row_cap), dim3(kWave), 0, st, B, vocab, cus,
+                         dt == PROPD_BF16 ? 1 : 0, tb, ws.logq);
   }
   if (!launch_ok()) return PROPD_ERR_DEVICE;
-  hipLaunchKernelGGL(prune_compact_kernel, dim3(B), dim3(PROPD_MAX_TREE), 0, st, T_max, top_k,
-                     tree->n_nodes, tree->parent, tree->token, tree->depth, tree->anc, ws.rank,
+  hipLaunchKernelGGL(prune_compact_kernel, dim3(B), dim3(PROPD_MAX_TREE * kCompactSplit), 0, st, B, T_max,
+                     vocab, cus, dt == PROPD_BF16 ? 1 : 0, crit, tree->n_nodes, tree->parent, tree->token,
+                     tree->depth, tree->anc, scored ? ws.row_base : nullptr, ws.cnt_part, ws.logq,
                      keep_bits, new_index, orig_index, n_kept, tree_out->n_nodes, tree_out->parent,
                      tree_out->token, tree_out->depth, tree_out->anc, rank_out);
   if (n_payloads > 0) {
@@ -1048,7 +1427,7 @@ extern "C" propd_status propd_early_prune(
     int32_t *rank_out, int32_t n_payloads, const propd_payload *payloads, void *workspace,
     size_t workspace_bytes, void *hip_stream) {
   if (top_k < 1) return PROPD_ERR_INVALID_ARG;
-  const Criterion crit = {0, top_k, 0.f, 0, nullptr};
+  const propd::Criterion crit = {0, top_k, 0.f, 0, nullptr};
   return prune_impl(crit, tree, dt, hidden, vocab, hidden_states, head_weight, keep_bits, new_index,
                     orig_index, n_kept, cu_nodes, tree_out, rank_out, n_payloads, payloads,
                     workspace, workspace_bytes, hip_stream);
@@ -1060,7 +1439,7 @@ extern "C" propd_status propd_early_prune_prob(
     uint64_t *keep_bits, int32_t *new_index, int32_t *orig_index, int32_t *n_kept,
     int32_t *cu_nodes, const propd_tree_out *tree_out, float *log_marginal, int32_t n_payloads,
     const propd_payload *payloads, void *workspace, size_t workspace_bytes, void *hip_stream) {
-  Criterion crit = {1, 1, 0.f, 0, log_marginal};
+  propd::Criterion crit = {1, 1, 0.f, 0, log_marginal};
   if (mode == PROPD_PROB_THRESHOLD) {
     if (!(threshold >= 0.f) || threshold > 1.f) return PROPD_ERR_INVALID_ARG;
     crit.log_threshold = threshold > 0.f ? logf(threshold) : -INFINITY;

@@ -46,8 +46,8 @@ def test_status_strings(pb):
 
 def test_workspace_sizes(pb):
     assert pb.workspace_bytes(pb.WS_TREE_ATTENTION, 16, 128, 40, 128, 4096) > 0
-    big = pb.workspace_bytes(pb.WS_EARLY_PRUNE, 16, 128, hidden=5120, vocab=32000)
-    assert big >= 16 * 127 * 32000 * 4  # fp32 scores for every node that can have children
+    prune = pb.workspace_bytes(pb.WS_EARLY_PRUNE, 16, 128, hidden=5120, vocab=32000)
+    assert 0 < prune < 16 * 127 * 32000 * 4 // 8  # the scores themselves are never stored
     assert pb.workspace_bytes(pb.WS_ACCEPT_PATH, 16, 128, vocab=32000) >= 16 * 128 * 8
     assert pb.workspace_bytes(pb.WS_ACCEPT_PATH, 16, 129, vocab=32000) == 0  # tree too large
     assert pb.workspace_bytes(7, 16, 128) == 0
@@ -85,6 +85,13 @@ def test_bad_scalars_are_rejected_on_the_host(pb):
                                  None, fake, 16, None) == WORKSPACE
     assert lib.propd_early_prune(t, pb.PROPD_BF16, 128, 1000, 4, fake, fake, *outs, o, None, 9,
                                  None, fake, 1 << 30, None) == INVALID
+    odd = ctypes.c_void_p(0x1008)   # operand rows are fetched 16 bytes at a time
+    assert lib.propd_early_prune(t, pb.PROPD_BF16, 128, 1000, 4, odd, fake, *outs, o, None, 0,
+                                 None, fake, 1 << 30, None) == INVALID
+    assert lib.propd_early_prune(t, pb.PROPD_BF16, 128, 1000, 4, fake, odd, *outs, o, None, 0,
+                                 None, fake, 1 << 30, None) == INVALID
+    assert lib.propd_tree_attention(t, pb.PROPD_BF16, 1, 128, 1.0, odd, *args[1:], fake, 1 << 30, None) \
+        == INVALID
     # probability criterion: unknown mode, threshold outside [0,1], keep count below 1
     prob = lambda mode, thr, keep, ws_bytes=1 << 30: lib.propd_early_prune_prob(
         t, pb.PROPD_BF16, 128, 1000, mode, thr, keep, fake, fake, *outs, o, None, 0, None, fake,
