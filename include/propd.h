@@ -216,6 +216,24 @@ PROPD_API propd_status propd_accept_path(const propd_tree *tree, propd_dtype dt,
                                size_t workspace_bytes, void *hip_stream);
 
 /*
+ * propd_accept_path for callers that cannot allocate device memory or pass a workspace:
+ * code under HIP graph capture, serving loops and harnesses that forbid hipMalloc.  Same
+ * arguments, results and errors as propd_accept_path, minus the workspace: the partial
+ * arg-max records go to a fixed array in device memory that belongs to the library (one
+ * copy per GPU, PROPD_STATIC_ACCEPT_MAX_NODES * 64 bytes = 512 KB, held until the process
+ * ends).  The call allocates nothing and frees nothing.
+ *   - B * T_max must not exceed PROPD_STATIC_ACCEPT_MAX_NODES: PROPD_ERR_UNSUPPORTED otherwise.
+ *   - hip_stream must belong to the device that is current when the call is made.
+ *   - Every call on a GPU uses that GPU's one array: calls that may overlap on one GPU
+ *     (different streams, different threads) race.  Nothing in it has to be cleared
+ *     between calls: a call reads only records it has written itself.
+ */
+#define PROPD_STATIC_ACCEPT_MAX_NODES 8192
+PROPD_API propd_status propd_accept_path_static(const propd_tree *tree, propd_dtype dt, int32_t vocab,
+                               const void *logits, int32_t *accept_len, int32_t *accept_path,
+                               int32_t path_stride, int32_t *next_token, void *hip_stream);
+
+/*
  * Early pruning by the probability-based criterion (Section 4.1, "Pruning Criterion", the
  * second of the two criteria; the paper sets it aside because its implementation moved the
  * probabilities to the host - here everything stays on the device).  The early head's scores

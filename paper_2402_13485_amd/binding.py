@@ -24,7 +24,7 @@ MAX_TREE = 128
 MAX_PAYLOADS = 8
 
 EXPORTS = ("propd_tree_mask", "propd_validate_tree", "propd_tree_attention", "propd_early_prune", "propd_accept_path",
-           "propd_early_prune_prob", "propd_commit_path", "propd_workspace_bytes", "propd_status_string",
+           "propd_accept_path_static", "propd_early_prune_prob", "propd_commit_path", "propd_workspace_bytes", "propd_status_string",
            "propd_controller_bytes", "propd_controller_init", "propd_controller_observe_time",
            "propd_controller_observe_hit", "propd_controller_fit", "propd_controller_build_tree",
            "propd_controller_best_size")
@@ -80,6 +80,9 @@ def load_library() -> ctypes.CDLL:
     lib.propd_accept_path.restype = ctypes.c_int
     lib.propd_accept_path.argtypes = [ctypes.POINTER(_Tree), ctypes.c_int, i32, vp, vp, vp, i32, vp,
                                       vp, sz, vp]
+    lib.propd_accept_path_static.restype = ctypes.c_int
+    lib.propd_accept_path_static.argtypes = [ctypes.POINTER(_Tree), ctypes.c_int, i32, vp, vp, vp, i32,
+                                             vp, vp]
     lib.propd_commit_path.restype = ctypes.c_int
     lib.propd_commit_path.argtypes = [ctypes.POINTER(_Tree), ctypes.c_int, i32, i32, vp, vp, i32, vp,
                                       vp, vp, vp, vp, i32, vp, vp, i32, vp]
@@ -362,6 +365,27 @@ def propd_accept_path(tree: Tree, logits: torch.Tensor, path_stride: Optional[in
         _ptr(next_token), _ptr(ws), ws.numel() * ws.element_size(), _stream()),
         "propd_accept_path")
     return accept_len, path, next_token
+
+
+STATIC_ACCEPT_MAX_NODES = 8192
+
+
+def propd_accept_path_static(tree: Tree, logits: torch.Tensor, accept_len: torch.Tensor,
+                             accept_path: torch.Tensor, next_token: torch.Tensor) -> None:
+    """The allocation-free form of ``propd_accept_path``: the caller passes every output
+    (int32 [B], [B,path_stride], [B]); the library's own fixed device array is the scratch."""
+    dt = _dt(logits)
+    B, T_max, vocab = logits.shape
+    _dev(logits, logits.dtype, "logits")
+    for t, name in ((accept_len, "accept_len"), (accept_path, "accept_path"), (next_token, "next_token")):
+        _dev(t, torch.int32, name)
+    if tree.B != B or tree.T_max != T_max or accept_len.numel() != B or next_token.numel() != B \
+            or accept_path.dim() != 2 or accept_path.shape[0] != B:
+        raise ValueError("accept_path_static: shapes disagree")
+    c_tree = tree._c()
+    _check(load_library().propd_accept_path_static(
+        ctypes.byref(c_tree), dt, vocab, _ptr(logits), _ptr(accept_len), _ptr(accept_path),
+        accept_path.shape[1], _ptr(next_token), _stream()), "propd_accept_path_static")
 
 
 def propd_commit_path(tree: Tree, accept_len: torch.Tensor, accept_path: torch.Tensor,

@@ -12,6 +12,8 @@
 //                       wave ballot, acceptance by testing the cached ancestor bitset
 //                       against the match bits, deepest accepted node by a workgroup
 //                       arg-max, path read off the winner's bitset.
+#include <mutex>
+
 #include "common.h"
 
 namespace propd {
@@ -332,4 +334,47 @@ extern "C" propd_status propd_accept_path(const propd_tree *tree, propd_dtype dt
   if (reinterpret_cast<uintptr_t>(workspace) % 8 != 0) return PROPD_ERR_INVALID_ARG;
   return accept_impl(tree, dt, vocab, logits, accept_len, accept_path, path_stride, next_token,
                      workspace, as_stream(hip_stream));
+}
+
+// ------------------------------------------------------------------------------------
+// The same call for callers that cannot allocate (code under graph capture, serving loops
+// that forbid hipMalloc): the partial arg-max records live in a fixed array in device
+// memory that belongs to the library, one copy per GPU.
+// ------------------------------------------------------------------------------------
+namespace {
+
+constexpr size_t kStaticNodes = PROPD_STATIC_ACCEPT_MAX_NODES;
+static __device__ __align__(256) unsigned char scratch[kStaticNodes * propd::kMaxSlices * sizeof(propd::RowPart)];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each GPU, once known
+
+// Device address of this GPU's copy of `scratch` (in host code the array's name is only a
+// handle for the runtime): looked up once per device, with that device current.
+void *static_scratch() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return nullptr;
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
+
+}  // namespace
+
+extern "C" propd_status propd_accept_path_static(const propd_tree *tree, propd_dtype dt, int32_t vocab,
+                                                 const void *logits, int32_t *accept_len,
+                                                 int32_t *accept_path, int32_t path_stride,
+                                                 int32_t *next_token, void *hip_stream) {
+  const propd_status ok = accept_check(tree, dt, vocab, logits, accept_len, accept_path, path_stride, next_token);
+  if (ok != PROPD_OK) return ok;
+  if ((size_t)tree->B * (size_t)tree->T_max > kStaticNodes) return PROPD_ERR_UNSUPPORTED;
+  void *ptr = static_scratch();
+  if (!ptr) return PROPD_ERR_DEVICE;
+  return accept_impl(tree, dt, vocab, logits, accept_len, accept_path, path_stride, next_token, ptr,
+                     as_stream(hip_stream));
 }

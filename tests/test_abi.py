@@ -121,6 +121,13 @@ def test_bad_scalars_are_rejected_on_the_host(pb):
                                  None) == INVALID
     assert lib.propd_accept_path(t, pb.PROPD_BF16, 100, fake, fake, fake, 8, fake, None, 0,
                                  None) == WORKSPACE
+    # the form without a workspace: same scalar checks; a batch beyond its fixed array is refused
+    assert lib.propd_accept_path_static(t, pb.PROPD_BF16, 0, fake, fake, fake, 8, fake, None) == INVALID
+    assert lib.propd_accept_path_static(t, 7, 100, fake, fake, fake, 8, fake, None) == INVALID
+    big = pb._Tree(65, 128, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000)
+    assert 65 * 128 > pb.STATIC_ACCEPT_MAX_NODES
+    assert lib.propd_accept_path_static(ctypes.byref(big), pb.PROPD_BF16, 100, fake, fake, fake, 8,
+                                        fake, None) == UNSUPPORTED
 
 
 def test_binding_has_no_fallback(pb, monkeypatch):
