@@ -28,6 +28,7 @@
 //   cu_nodes_kernel       exclusive prefix sum of survivor counts (when there are payloads
 //                         it rides along as one extra block of the gather launch)
 //   gather_rows_kernel    survivor rows of the listed payload tensors
+#include <cstdlib>
 #include <type_traits>
 #include <utility>
 
@@ -50,7 +51,7 @@ struct PruneScratch {
   float *own;           // [B*T_max]  z_parent[token] of every non-root node
   float *logq;          // [B*T_max]  probability criterion: log q of every node's token
   float *lse_part;      // [row_cap * parts][2]  probability criterion: (max, sum exp) per tile
-  int32_t *cnt_part;    // [parts / 2][B*T_max]  top-k criterion: per column tile, the scores of the
+  int32_t *cnt_part;    // [vocab / 128][B*T_max]  top-k criterion: per column tile, the scores of the
                         //                       parent's row that beat the node's token
   size_t row_cap, parts, total_bytes;
 };
@@ -76,11 +77,11 @@ static PruneScratch carve_scratch(void *base, int B, int T_max, int vocab) {
   s.own = reinterpret_cast<float *>(take(nt * 4));
   s.logq = reinterpret_cast<float *>(take(nt * 4));
   s.row_cap = (size_t)B * (T_max > 1 ? T_max - 1 : 1);  // a node with children is not a leaf
-  // column parts of a row: two per 128-wide tile (the narrowest MFMA tile, one per wave
-  // column), which also covers the 256-wide slices of the fp32 kernel
-  s.parts = 2 * (((size_t)vocab + 127) / 128);
+  // column parts of a row: one per wave column of a tile, at most four per 256 columns (two
+  // per 128-wide tile, four per 256-wide tile; the fp32 kernel has one per 256-wide slice)
+  s.parts = 4 * (((size_t)vocab + 255) / 256);
   s.lse_part = reinterpret_cast<float *>(take(s.row_cap * s.parts * 8));
-  s.cnt_part = reinterpret_cast<int32_t *>(take((s.parts / 2) * nt * 4));
+  s.cnt_part = reinterpret_cast<int32_t *>(take((((size_t)vocab + 127) / 128) * nt * 4));
   s.total_bytes = off;
   return s;
 }
@@ -856,17 +857,54 @@ __device__ __forceinline__ void early_head_tile(
     epilogue_lse<FN>(acc, m0, v0, m_total, vocab, n_tile, wm, wn, lane, tb);
 }
 
+#include "early_head_tall.h"
+
+// Which tile shape a call uses: decided on the device by every workgroup (and by the kernels
+// that read the per-tile results) from the row count, which the host never sees.  The cost of
+// a shape is rounds of workgroups over the compute units x tile area, the tall shape's area
+// weighted by what it was measured to cost per output relative to the other.
+struct HeadPlan {
+  int tall;     // 1: 352 x 256 tiles, 0: 256 x 64*fn tiles
+  int fn;
+  int m_tiles, n_tiles;
+  int n_parts;  // column parts per row that the epilogue writes
+};
+constexpr int kTallCostPercent = 85;
+
+__host__ __device__ inline HeadPlan head_plan(int m_total, int vocab, int cus, int force) {
+  HeadPlan pl;
+  pl.tall = 0;
+  pl.m_tiles = (m_total + kGemmBM - 1) / kGemmBM;
+  pl.fn = gemm_pick_fn(pl.m_tiles > 0 ? pl.m_tiles : 1, vocab, cus);
+  pl.n_tiles = (vocab + 64 * pl.fn - 1) / (64 * pl.fn);
+  pl.n_parts = 2 * pl.n_tiles;
+  if (m_total <= 0) return pl;
+  const long long rounds = ((long long)pl.m_tiles * pl.n_tiles + cus - 1) / cus;
+  const long long cost = rounds * kGemmBM * 64 * pl.fn * 100;
+  const int mt = (m_total + kTallBM - 1) / kTallBM, nt = (vocab + kTallBN - 1) / kTallBN;
+  const long long rounds_tall = ((long long)mt * nt + cus - 1) / cus;
+  const long long cost_tall = rounds_tall * kTallBM * kTallBN * kTallCostPercent;
+  if (force == 2 || (force == 0 && cost_tall < cost)) {
+    pl.tall = 1;
+    pl.m_tiles = mt;
+    pl.n_tiles = nt;
+    pl.n_parts = 4 * nt;
+  }
+  return pl;
+}
+
+constexpr int kHeadLdsBytes = kTallLdsBytes > kGemmLdsBytes ? kTallLdsBytes : kGemmLdsBytes;
+
 // Persistent over the tiles: tile -> (xcd, slot) as described above, a workgroup takes tiles
 // blockIdx.x, blockIdx.x + gridDim.x, ... (the grid is a multiple of the XCD count).
 template <int KIND>
 __global__ __launch_bounds__(kGemmThreads, 1) void early_head_bf16_kernel(
-    int hidden, int vocab, int B, int cus, const uint16_t *__restrict__ hidden_states,
+    int hidden, int vocab, int B, int cus, int force, const uint16_t *__restrict__ hidden_states,
     const uint16_t *__restrict__ head_weight, HeadTables tb) {
   const int m_total = tb.row_base[B];
-  const int m_tiles = (m_total + kGemmBM - 1) / kGemmBM;
-  if (m_tiles == 0) return;
-  const int fn = gemm_pick_fn(m_tiles, vocab, cus);
-  const int n_tiles = (vocab + 64 * fn - 1) / (64 * fn);
+  if (m_total <= 0) return;
+  const HeadPlan pl = head_plan(m_total, vocab, cus, force);
+  const int m_tiles = pl.m_tiles, n_tiles = pl.n_tiles;
   const long long total = (long long)kXcds * ((n_tiles + kXcds - 1) / kXcds) * m_tiles;
   extern __shared__ __attribute__((aligned(1024))) unsigned char gemm_smem[];
   for (long long tile = blockIdx.x; tile < total; tile += gridDim.x) {
@@ -874,10 +912,16 @@ __global__ __launch_bounds__(kGemmThreads, 1) void early_head_bf16_kernel(
     const long long slot = tile / kXcds;
     const int n_tile = (int)(slot / m_tiles) * kXcds + xcd;
     if (n_tile >= n_tiles) continue;
-    const int m0 = (int)(slot % m_tiles) * kGemmBM, v0 = n_tile * 64 * fn;
-    if (fn == 2)
+    const int m_tile = (int)(slot % m_tiles);
+    if (pl.tall) {
+      early_head_tall_tile<KIND>(hidden, vocab, m_total, m_tile * kTallBM, n_tile * kTallBN, n_tile,
+                                 hidden_states, head_weight, tb, gemm_smem);
+      continue;
+    }
+    const int m0 = m_tile * kGemmBM, v0 = n_tile * 64 * pl.fn;
+    if (pl.fn == 2)
       early_head_tile<2, KIND>(hidden, vocab, m_total, m0, v0, n_tile, hidden_states, head_weight, tb, gemm_smem);
-    else if (fn == 3)
+    else if (pl.fn == 3)
       early_head_tile<3, KIND>(hidden, vocab, m_total, m0, v0, n_tile, hidden_states, head_weight, tb, gemm_smem);
     else
       early_head_tile<4, KIND>(hidden, vocab, m_total, m0, v0, n_tile, hidden_states, head_weight, tb, gemm_smem);
@@ -940,15 +984,14 @@ __global__ __launch_bounds__(256) void early_head_f32_kernel(
 // One wave per score row: log sum_v exp(z[v]) from the row's tile partials (the first
 // n_parts of them were written), then logq = own score - that for every child of the
 // row's node.  A token id outside the vocabulary has probability 0 (logq = -inf).
-__global__ __launch_bounds__(kWave) void row_lse_kernel(int B, int vocab, int cus, int bf16,
+__global__ __launch_bounds__(kWave) void row_lse_kernel(int B, int vocab, int cus, int force, int bf16,
                                                         HeadTables tb, float *__restrict__ logq) {
   const int m = blockIdx.x;
   const int m_total = tb.row_base[B];
   if (m >= m_total) return;
   int n_parts;
   if (bf16) {
-    const int fn = gemm_pick_fn((m_total + kGemmBM - 1) / kGemmBM, vocab, cus);
-    n_parts = 2 * ((vocab + 64 * fn - 1) / (64 * fn));
+    n_parts = head_plan(m_total, vocab, cus, force).n_parts;
   } else {
     n_parts = (vocab + 255) / 256;
   }
@@ -993,7 +1036,7 @@ struct Criterion {
 constexpr int kCompactSplit = 4;  // threads that add up one node's per-tile counts
 
 __global__ __launch_bounds__(PROPD_MAX_TREE * kCompactSplit) void prune_compact_kernel(
-    int B, int T_max, int vocab, int cus, int bf16, Criterion crit, const int32_t *__restrict__ n_nodes,
+    int B, int T_max, int vocab, int cus, int force, int bf16, Criterion crit, const int32_t *__restrict__ n_nodes,
     const int32_t *__restrict__ parent, const int32_t *__restrict__ token,
     const int32_t *__restrict__ depth, const uint64_t *__restrict__ anc,
     const int32_t *__restrict__ row_base, const int32_t *__restrict__ cnt_part,
@@ -1016,8 +1059,7 @@ __global__ __launch_bounds__(PROPD_MAX_TREE * kCompactSplit) void prune_compact_
     if (row_base) {
       const int m_total = row_base[B];
       if (bf16) {
-        const int m_tiles = (m_total + kGemmBM - 1) / kGemmBM;
-        if (m_tiles > 0) n_tiles = (vocab + 64 * gemm_pick_fn(m_tiles, vocab, cus) - 1) / (64 * gemm_pick_fn(m_tiles, vocab, cus));
+        if (m_total > 0) n_tiles = head_plan(m_total, vocab, cus, force).n_tiles;
       } else if (m_total > 0) {
         n_tiles = (vocab + 255) / 256;
       }
@@ -1321,6 +1363,10 @@ static propd_status prune_impl(
   PruneScratch ws = carve_scratch(workspace, B, T_max, vocab);
   hipStream_t st = as_stream(hip_stream);
 
+  static const int force = [] {  // tile-shape override for tuning runs: 1 = 256-row tiles, 2 = 352-row tiles
+    const char *e = getenv("PROPD_HEAD_PLAN");
+    return e ? atoi(e) : 0;
+  }();
   const bool scored = !(crit.kind == 0 && crit.top_k >= vocab);
   // top_k >= vocab: every id of the vocabulary is inside the list, no scores are needed (ids
   // outside the vocabulary still fail, in the decision kernel)
@@ -1367,9 +1413,9 @@ static propd_status prune_impl(
       static bool attr_set = false;
       if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(&early_head_bf16_kernel<0>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes) != hipSuccess ||
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kHeadLdsBytes) != hipSuccess ||
             hipFuncSetAttribute(reinterpret_cast<const void *>(&early_head_bf16_kernel<1>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes) != hipSuccess)
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kHeadLdsBytes) != hipSuccess)
           return PROPD_ERR_DEVICE;
         attr_set = true;
       }
@@ -1381,12 +1427,12 @@ static propd_status prune_impl(
       const long long persistent = (2ll * cus + kXcds - 1) / kXcds * kXcds;
       grid = grid < persistent ? grid : persistent;
       if (crit.kind == 0)
-        hipLaunchKernelGGL(early_head_bf16_kernel<0>, dim3((unsigned)grid), dim3(kGemmThreads), kGemmLdsBytes, st,
-                           hidden, vocab, B, cus, reinterpret_cast<const uint16_t *>(hidden_states),
+        hipLaunchKernelGGL(early_head_bf16_kernel<0>, dim3((unsigned)grid), dim3(kGemmThreads), kHeadLdsBytes, st,
+                           hidden, vocab, B, cus, force, reinterpret_cast<const uint16_t *>(hidden_states),
                            reinterpret_cast<const uint16_t *>(head_weight), tb);
       else
-        hipLaunchKernelGGL(early_head_bf16_kernel<1>, dim3((unsigned)grid), dim3(kGemmThreads), kGemmLdsBytes, st,
-                           hidden, vocab, B, cus, reinterpret_cast<const uint16_t *>(hidden_states),
+        hipLaunchKernelGGL(early_head_bf16_kernel<1>, dim3((unsigned)grid), dim3(kGemmThreads), kHeadLdsBytes, st,
+                           hidden, vocab, B, cus, force, reinterpret_cast<const uint16_t *>(hidden_states),
                            reinterpret_cast<const uint16_t *>(head_weight), tb);
     } else {
       dim3 grid((unsigned)ws.row_cap, (unsigned)((vocab + 255) / 256));
@@ -1400,12 +1446,12 @@ static propd_status prune_impl(
                            reinterpret_cast<const float *>(head_weight), tb);
     }
     if (crit.kind != 0)
-      hipLaunchKernelGGL(row_lse_kernel, dim3((unsigned)ws.row_cap), dim3(kWave), 0, st, B, vocab, cus,
+      hipLaunchKernelGGL(row_lse_kernel, dim3((unsigned)ws.row_cap), dim3(kWave), 0, st, B, vocab, cus, force,
                          dt == PROPD_BF16 ? 1 : 0, tb, ws.logq);
   }
   if (!launch_ok()) return PROPD_ERR_DEVICE;
   hipLaunchKernelGGL(prune_compact_kernel, dim3(B), dim3(PROPD_MAX_TREE * kCompactSplit), 0, st, B, T_max,
-                     vocab, cus, dt == PROPD_BF16 ? 1 : 0, crit, tree->n_nodes, tree->parent, tree->token,
+                     vocab, cus, force, dt == PROPD_BF16 ? 1 : 0, crit, tree->n_nodes, tree->parent, tree->token,
                      tree->depth, tree->anc, scored ? ws.row_base : nullptr, ws.cnt_part, ws.logq,
                      keep_bits, new_index, orig_index, n_kept, tree_out->n_nodes, tree_out->parent,
                      tree_out->token, tree_out->depth, tree_out->anc, rank_out);
