@@ -13,8 +13,10 @@
 //   - 8 waves as 2 (rows) x 4 (columns), a wave owns 176 x 64 as 11 x 4 tiles of the
 //     16x16x32 bf16 MFMA (176 = 11 x 16 is no multiple of 32);
 //   - K advances 32 per step through a ring of four 38 KB LDS stages (352 + 256 rows of 64
-//     bytes, same XOR swizzle of the 16-byte chunks as the other shape), filled by direct
-//     global->LDS loads three steps ahead;
+//     bytes), filled by direct global->LDS loads three steps ahead.  The 16-byte chunks of a
+//     row are XOR-swizzled with key(row) = (row >> 1) & 3: a fragment read of this MFMA has
+//     lane -> (row lane % 16, chunk lane / 16), and with the other shape's key (row >> 2) & 3
+//     every such read took twice its time in bank conflicts (measured: 64 against 38 ticks);
 //   - per step a wave reads its four B fragments and then streams the eleven A fragments
 //     through a four-deep register ring: the read of fragment i + 3 is issued behind the four
 //     MFMAs of fragment i, waits are placed by hand (LDS reads return in order);
@@ -282,7 +284,7 @@ __device__ __forceinline__ void early_head_tall_tile(
 
   // ---- loader: group gi = wave + 8 j (16 rows, 1 KB) for j = 0 .. n_groups - 1
   const int ld_row = lane >> 2;
-  const int ld_chunk = ((lane & 3) ^ ((lane >> 4) & 3)) << 4;  // byte offset in the global row
+  const int ld_chunk = ((lane & 3) ^ ((lane >> 3) & 3)) << 4;  // byte offset in the global row: chunk ^ key(row)
   const int n_groups = wave + 32 < kTallGroups ? 5 : 4;         // loads of this wave per K step
   const unsigned char *src[5];
 #pragma unroll
@@ -310,7 +312,7 @@ __device__ __forceinline__ void early_head_tall_tile(
 
   // ---- per-lane LDS read addresses: row lane % 16 of a 16-row block, chunk lane / 16 (swizzled)
   const int c16 = lane & 15, kq = lane >> 4;
-  const uint32_t frag_off = c16 * kGemmRowBytes + ((kq ^ ((c16 >> 2) & 3)) << 4);
+  const uint32_t frag_off = c16 * kGemmRowBytes + ((kq ^ ((c16 >> 1) & 3)) << 4);
   const uint32_t a_rd = smem_base + wm * kTallWaveRows * kGemmRowBytes + frag_off;
   const uint32_t b_rd = smem_base + (kTallBM + wn * kTallWaveCols) * kGemmRowBytes + frag_off;
 
