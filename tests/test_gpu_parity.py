@@ -299,6 +299,58 @@ def test_prune_out_of_range_token_fails(pb):
     assert not (keep >> 3) & 1 and not (keep >> 5) & 1 and keep & 1
 
 
+def test_prune_tokens_that_nobody_placed(pb, oracle):
+    """Token ids drawn at random, not placed at a distance from the k boundary: the decisions must
+    agree with the oracle's wherever the oracle's own margin is at least tau, the counted ranks
+    may differ only where scores are nearly equal, and everything after the decision must be the
+    oracle's compaction of the GPU's own pass/fail flags."""
+    rng = np.random.default_rng(4242)
+    B, T_max, Hd, V, k, tau = 4, 64, 512, 4096, 2000, 1e-3
+    shapes = [synth.rank_product_tree(64, 4), synth.random_tree(rng, 64, max_depth=7),
+              synth.random_tree(rng, 33), synth.star_tree(40)]
+    n_nodes, parent, _ = synth.pad_trees(shapes, T_max)
+    token = synth.draw_tokens(rng, n_nodes, parent, V)
+    hidden = synth.normal_bf16(rng, (B, T_max, Hd))
+    weight = synth.normal_bf16(rng, (V, Hd), sigma=0.02)
+    x = dict(n_nodes=n_nodes, parent=parent, token=token, hidden_states=hidden, head_weight=weight, top_k=k)
+    res, sents = run_prune(pb, x, [hidden])
+    rank_ref, margin = oracle.early_head_rank(n_nodes, parent, token, hidden, weight, k)
+    rank = to_host(res.rank)
+    valid = rank_ref >= 0
+    sure = valid & (np.isfinite(margin)) & (margin >= tau)
+    assert sure.sum() > 0.8 * (valid.sum() - B)            # most decisions are far from the boundary
+    assert ((rank >= k) == (rank_ref >= k))[sure].all()
+    assert (rank[~valid] == -1).all() and (rank[:, 0] == 0).all()
+    diff = np.abs(rank - rank_ref)[valid]
+    assert diff.max() <= 3 and (diff > 0).mean() < 0.05     # fp32 against fp64 order of near-equal scores
+    assert 0.1 < (rank[valid] < k).mean() < 0.9
+    ref = oracle.prune_compact(n_nodes, parent, token, rank, k)   # the GPU's own flags
+    assert (u64(res.keep_bits) == ref["keep_bits"]).all()
+    for name in ("new_index", "orig_index", "n_kept", "cu_nodes"):
+        assert (to_host(getattr(res, name)) == ref[name]).all(), name
+    for name in ("parent", "token", "depth"):
+        assert (to_host(getattr(res.tree, name)) == ref[name]).all(), name
+    assert (u64(res.tree.anc) == ref["anc"]).all()
+    want = oracle.gather_rows(hidden, ref["orig_index"], ref["n_kept"], fill_from=sents[0])
+    assert (to_host(res.payloads[0]) == want).all()
+
+
+def test_prune_without_rank_output_gives_the_same_decisions(pb, oracle):
+    """The call as a decoding loop makes it (no rank output asked for) on a batch whose score rows
+    fill more than one row tile of either tile shape."""
+    w = synth.Workload(77, "case", "bf16", 7, 1, 128, 128, 256, 2048, 6, 1e-3)
+    x = synth.make_prune_inputs(w, trees=[synth.rank_product_tree(128, 5)] * 4 +
+                                [synth.chain_tree(128), synth.star_tree(100), synth.chain_tree(128)])
+    res, _ = run_prune(pb, x, want_rank=False)
+    rank_ref, margin = oracle.early_head_rank(x["n_nodes"], x["parent"], x["token"], x["hidden_states"],
+                                              x["head_weight"], x["top_k"])
+    assert margin[np.isfinite(margin)].min() >= 0.999e-3
+    ref = oracle.prune_compact(x["n_nodes"], x["parent"], x["token"], rank_ref, x["top_k"])
+    assert res.rank is None and (u64(res.keep_bits) == ref["keep_bits"]).all()
+    assert (to_host(res.orig_index) == ref["orig_index"]).all()
+    assert (u64(res.tree.anc) == ref["anc"]).all()
+
+
 # ------------------------------------------------------------------ accept
 
 
@@ -398,6 +450,61 @@ def test_whole_step_reduced_c3(pb, oracle):
                                                g(acc["logits"]))
     assert (to_host(alen) == r_len).all() and (to_host(path) == r_path).all()
     assert (to_host(nxt) == r_next).all()
+
+
+def test_layers_before_and_after_the_pruning_point(pb, oracle):
+    """Figure 5 at reduced size: two layers of tree attention on the full tree, the pruning pass,
+    two layers on the compacted tree, acceptance; every layer has its own K/V cache and its own
+    tree q/k/v, the later layers' tensors reach the compacted tree as payloads of the pruning call.
+    Every layer's output against the oracle, and (Section 4.1: pruning does not change what a
+    surviving node computes) the later layers' survivors against the same layers run unpruned."""
+    w = synth.Workload(31, "layers", "bf16", 3, 3, 128, 64, 256, 2048, 8, 1e-3)
+    trees = [synth.rank_product_tree(64, 4), synth.rank_product_tree(64, 4), synth.chain_tree(20)]
+    seq = np.array([333, 64, 700], np.int32)
+    n_layers, n_full = 4, 2
+    layers = []
+    for l in range(n_layers):
+        wl = synth.Workload(310 + l, "layers", "bf16", 3, 3, 128, 64, 256, 2048, 8, 1e-3)
+        layers.append(synth.make_attention_inputs(wl, seq_lens=seq, trees=trees))
+    xp = synth.make_prune_inputs(w, trees=trees)
+    acc = synth.make_accept_inputs(w, xp["n_nodes"], xp["parent"], xp["token"])
+    tree = dev_tree(pb, xp["n_nodes"], xp["parent"], xp["token"])
+    seq_d = to_dev(seq)
+    dev = [{k: to_dev(x[k]) for k in ("q", "k_cache", "v_cache", "k_tree", "v_tree")} for x in layers]
+    outs_full = []
+    for l in range(n_layers):            # every layer on the full tree (the later ones for reference)
+        sent = sentinel_like(layers[l]["q"])
+        out = to_dev(sent)
+        d = dev[l]
+        pb.propd_tree_attention(tree, d["q"], d["k_cache"], d["v_cache"], d["k_tree"], d["v_tree"], seq_d,
+                                layers[l]["scale"], out=out)
+        torch.cuda.synchronize()
+        if l < n_full:
+            check_attention(oracle, layers[l], out, sent)
+        outs_full.append(host_f64(out))
+    payload_names = [(l, name) for l in range(n_full, n_layers) for name in ("q", "k_tree", "v_tree")]
+    payload_host = [layers[l][name] for l, name in payload_names] + [acc["logits"]]
+    res, sents = run_prune(pb, xp, payload_host)
+    ref, _ = check_prune(oracle, xp, res, payload_host, sents)
+    g = lambda a: oracle.gather_rows(a, ref["orig_index"], ref["n_kept"], fill_from=a)
+    for n, l in enumerate(range(n_full, n_layers)):
+        q2, kt2, vt2 = res.payloads[3 * n: 3 * n + 3]
+        sent = sentinel_like(layers[l]["q"])
+        out = to_dev(sent)
+        pb.propd_tree_attention(res.tree, q2, dev[l]["k_cache"], dev[l]["v_cache"], kt2, vt2, seq_d,
+                                layers[l]["scale"], out=out)
+        torch.cuda.synchronize()
+        y = dict(layers[l], n_nodes=ref["n_kept"], parent=ref["parent"], q=g(layers[l]["q"]),
+                 k_tree=g(layers[l]["k_tree"]), v_tree=g(layers[l]["v_tree"]))
+        check_attention(oracle, y, out, sent)
+        got = host_f64(out)
+        for b in range(3):
+            n_b = int(ref["n_kept"][b])
+            assert np.abs(got[b, :, :n_b] - outs_full[l][b][:, ref["orig_index"][b, :n_b]]).max() <= 2e-2
+    alen, path, nxt = pb.propd_accept_path(res.tree, res.payloads[-1])
+    torch.cuda.synchronize()
+    r_len, r_path, r_next = oracle.accept_path(ref["n_kept"], ref["parent"], ref["token"], g(acc["logits"]))
+    assert (to_host(alen) == r_len).all() and (to_host(path) == r_path).all() and (to_host(nxt) == r_next).all()
 
 
 # ------------------------------------------------------------------ scratch bounds
