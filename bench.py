@@ -26,6 +26,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, vendor figure
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA, vendor figure
 
 
 def log(msg: str) -> None:
@@ -134,7 +135,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", type=int, default=4, choices=[2, 3, 4, 5])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-seconds", type=float, default=15.0,
+    ap.add_argument("--cpu-seconds", type=float, default=10.0,
                     help="CPU work the oracle baseline is bounded to (whole sequences)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain 1 GiB device copy (the reference kernel that the "
@@ -193,12 +194,17 @@ def main() -> int:
 
     parts = np.array([[m[i].elapsed_time(m[i + 1]) for i in range(4)] for m in marks])  # ms
     att_full_ms, prune_ms, att_small_ms, accept_ms = parts.mean(axis=0)
+    part_names = ("attention_full_tree", "early_prune", "attention_compacted_tree", "accept")
+    pct = lambda a: {"median": float(np.median(a)) * 1e3, "p10": float(np.percentile(a, 10)) * 1e3,
+                     "p90": float(np.percentile(a, 90)) * 1e3}
+    step_ms_events = np.array([m[0].elapsed_time(m[4]) for m in marks])  # GPU time of each step
     sum_T = int(att["n_nodes"].sum())
     kv_bytes = float(sum(int(L) for L in att["seq_lens"])) * H * d * 2 * 2
     side_bytes = float(sum_T) * H * d * 2 * 4  # q, k_tree, v_tree read; out written
     alg_bytes = kv_bytes + side_bytes
     achieved = alg_bytes / (att_full_ms * 1e-3) / 1e9
     accept_len = to_host(last[0])
+    recorded = recorded_profile(w.name)
 
     # what a decoding loop does next (outside the metric's step): commit of the accepted path.
     # Timed on lengths lowered by the path stride so that every accepted row has room; it
@@ -218,6 +224,21 @@ def main() -> int:
         commit_ms.append(e0.elapsed_time(e1))
     commit_us = float(np.median(commit_ms[5:])) * 1e3
 
+    # the early head as a dense contraction: 2 * M * hidden * vocab with M = nodes that have children
+    head = None
+    if prune:
+        n_par = sum(len(set(int(p) for p in att["parent"][b, 1:int(T)])) for b, T in enumerate(att["n_nodes"]))
+        flop = 2.0 * n_par * w.hidden * w.vocab
+        k_us = recorded.get("early_head_kernel_us")
+        head = {"kernel": "early_head_bf16_kernel inside propd_early_prune", "bound": "mfma",
+                "rows": n_par, "flop": flop, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "call_us": prune_ms * 1e3,
+                "achieved_call": flop / (prune_ms * 1e-3) / 1e12,
+                "frac_call": flop / (prune_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                "kernel_us_recorded": k_us,
+                "frac_kernel_recorded": None if not k_us else flop / (k_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+
+    k_att = recorded.get("tree_attn_kernel_us")
     result = {
         "metric": "verified tree tokens/s (B*T)",
         "value": sum_T / (ms_per_step * 1e-3),
@@ -231,19 +252,29 @@ def main() -> int:
                    "vocab": w.vocab, "top_k": w.top_k,
                    "survivors": int(np.sum(n_kept_host)),
                    "mean_accept_len": float(accept_len.mean())},
+        "step_us": pct(step_ms_events),
         "parts_us": {"attention_full_tree": att_full_ms * 1e3, "early_prune": prune_ms * 1e3,
                      "attention_compacted_tree": att_small_ms * 1e3, "accept": accept_ms * 1e3,
                      "commit_outside_step": commit_us},
-        "roofline": {"kernel": "propd_tree_attention on the full tree: tree_attn_bf16_kernel "
-                               "+ tree_attn_combine_kernel", "bound": "hbm",
+        "parts_us_percentiles": {n: pct(parts[:, i]) for i, n in enumerate(part_names)},
+        "roofline": {"kernel": "tree_attn_bf16_kernel (+ tree_attn_combine_kernel): "
+                               "propd_tree_attention on the full tree", "bound": "hbm",
+                     # achieved: the whole call (both kernels and the gap between them), HIP
+                     # events on the launch stream in this run
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": recorded_traffic(w.name),
+                     "traffic": recorded.get("traffic_bytes_per_launch"),
                      "algorithmic_bytes": alg_bytes,
+                     "call_us": att_full_ms * 1e3,
+                     "call_us_median": float(np.median(parts[:, 0])) * 1e3,
+                     # the dominant kernel alone, from the kernel trace kept under profiles/
+                     "kernel_us_recorded": k_att,
+                     "frac_kernel_recorded": None if not k_att else alg_bytes / (k_att * 1e-6) / 1e9 / HBM_PEAK_GBPS,
                      "kv_stream_gbps": kv_bytes / (att_full_ms * 1e-3) / 1e9,
                      "kv_stream_frac": kv_bytes / (att_full_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
                      "compacted_tree_kv_gbps": kv_bytes / (att_small_ms * 1e-3) / 1e9
                      if prune else None},
+        "early_head": head,
     }
 
     if not args.no_cpu_baseline:
@@ -375,19 +406,25 @@ def multi_layer_table(w, args, torch, pb, synth):
     return 0
 
 
-def recorded_traffic(workload_name):
-    """HBM bytes per full-tree attention launch, from the rocprofv3 counter runs summarised
-    under profiles/ (FETCH_SIZE + WRITE_SIZE, scaled by the copy-kernel calibration); None if
-    no such summary exists for this workload."""
-    path = os.path.join(ROOT, "profiles", f"{workload_name}_tree_attention_hbm_traffic.txt")
-    try:
-        with open(path) as f:
-            for line in f:
-                if line.startswith("traffic_bytes_per_launch"):
-                    return float(line.split("=")[1])
-    except OSError:
-        pass
-    return None
+def recorded_profile(workload_name):
+    """Figures kept under profiles/ from rocprofv3 runs of this same command, as `key = value`
+    lines: HBM bytes per full-tree attention launch (FETCH_SIZE + WRITE_SIZE scaled by the
+    copy-kernel calibration) and average kernel durations from the kernel trace.  Missing
+    files or keys give an empty entry."""
+    out = {}
+    for name in (f"{workload_name}_tree_attention_hbm_traffic.txt", f"{workload_name}_recorded_kernel_us.txt"):
+        try:
+            with open(os.path.join(ROOT, "profiles", name)) as f:
+                for line in f:
+                    if "=" in line and not line.startswith("#"):
+                        k, v = line.split("=", 1)
+                        try:
+                            out[k.strip()] = float(v)
+                        except ValueError:
+                            pass
+        except OSError:
+            pass
+    return out
 
 
 def copy_calibration(torch):
@@ -405,14 +442,13 @@ def copy_calibration(torch):
 def cpu_baseline(w, att, pr, acc, token, budget_s):
     """The oracle, as it stands, timed on this host on a bounded sample of the workload: whole
     sequences (all heads) through the same four parts, one sequence at a time, until about
-    `budget_s` seconds of CPU work are spent.  A reported baseline only."""
+    `budget_s` seconds of CPU work are spent on all cores; then the first sequence once more on
+    ONE thread.  A reported baseline only."""
     from oracle import oracle
     oracle.build()
-    secs = {"attention_full_tree": 0.0, "early_prune": 0.0, "attention_compacted_tree": 0.0,
-            "accept": 0.0}
-    done_tokens, done_seqs = 0, 0
-    t_begin = time.perf_counter()
-    for b in range(w.B):
+    part_names = ("attention_full_tree", "early_prune", "attention_compacted_tree", "accept")
+
+    def one_sequence(b, secs):
         sl = slice(b, b + 1)
         cut = lambda a: np.ascontiguousarray(a[sl])
         n_nodes, parent, seq = att["n_nodes"][sl], att["parent"][sl], att["seq_lens"][sl]
@@ -439,19 +475,39 @@ def cpu_baseline(w, att, pr, acc, token, budget_s):
         t0 = time.perf_counter()
         oracle.accept_path(tree2[0], tree2[1], tree2[2], logits)
         secs["accept"] += time.perf_counter() - t0
-        done_tokens += int(n_nodes.sum())
+        return int(n_nodes.sum())
+
+    all_cores = oracle.threads()
+    secs = dict.fromkeys(part_names, 0.0)
+    done_tokens, done_seqs = 0, 0
+    t_begin = time.perf_counter()
+    for b in range(w.B):
+        done_tokens += one_sequence(b, secs)
         done_seqs += 1
         spent = time.perf_counter() - t_begin
-        log(f"cpu baseline: sequence {b} done, {spent:.1f}s")
-        if spent >= budget_s or spent * (done_seqs + 1) / done_seqs > 2.0 * budget_s:
+        log(f"cpu baseline ({all_cores} threads): sequence {b} done, {spent:.1f}s")
+        if spent >= budget_s or spent * (done_seqs + 1) / done_seqs > 1.5 * budget_s:
             break
     total = sum(secs.values())
     secs["total"] = total
-    return {"value": done_tokens / total, "unit": "tokens/s", "cores": oracle.threads(),
+    # the same on one thread: the first sequence only (all heads)
+    one = dict.fromkeys(part_names, 0.0)
+    oracle.set_threads(1)
+    try:
+        one_tokens = one_sequence(0, one)
+    finally:
+        oracle.set_threads(all_cores)
+    one_total = sum(one.values())
+    one["total"] = one_total
+    log(f"cpu baseline (1 thread): sequence 0 done, {one_total:.1f}s")
+    return {"value": done_tokens / total, "unit": "tokens/s", "cores": all_cores,
             "kind": "oracle",
             "sample": f"the first {done_seqs} of {w.B} sequences, all heads, through the same "
-                      f"four parts ({done_tokens} tree tokens, {total:.1f} s)",
-            "seconds": secs}
+                      f"four parts ({done_tokens} tree tokens, {total:.1f} s); and sequence 0 again "
+                      f"on one thread ({one_tokens} tree tokens, {one_total:.1f} s)",
+            "seconds": secs,
+            "one_thread": {"value": one_tokens / one_total, "unit": "tokens/s", "cores": 1,
+                           "seconds": one}}
 
 
 if __name__ == "__main__":

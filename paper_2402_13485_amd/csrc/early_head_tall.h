@@ -322,8 +322,13 @@ __device__ __forceinline__ void early_head_tall_tile(
 #pragma unroll
     for (int j = 0; j < kTallNJ; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+  // The ring: the step being multiplied, the next one (landed or landing) and one or two more
+  // in flight.  The loads of step s + 3 are issued in the MIDDLE of step s, into the slot that
+  // step s - 1 left at the last barrier: the address arithmetic and the issue then run in the
+  // shadow of this wave's queued MFMAs instead of right after the barrier, where every wave
+  // of the workgroup would do them at the same time with the matrix cores idle.
   const int n_steps = hidden / kBK;
-  const int n_pro = n_steps < kTallStages ? n_steps : kTallStages;
+  const int n_pro = n_steps < kTallStages - 1 ? n_steps : kTallStages - 1;
   int slot_ld = 0;
   for (int i = 0; i < n_pro; ++i) {
     issue(slot_ld);
@@ -335,34 +340,38 @@ __device__ __forceinline__ void early_head_tall_tile(
   for (int step = 0; step < n_steps; ++step) {
     const uint32_t pa = a_rd + so, pb = b_rd + so;
     u32x4 bf[kTallNJ], af[4];
+    // the first product needs only A0 and B0: they are read first
+    af[0] = gemm_lds_read16<0>(pa);
     bf[0] = gemm_lds_read16<0>(pb);
     bf[1] = gemm_lds_read16<1024>(pb);
     bf[2] = gemm_lds_read16<2048>(pb);
     bf[3] = gemm_lds_read16<3072>(pb);
-    af[0] = gemm_lds_read16<0>(pa);
     af[1] = gemm_lds_read16<1024>(pa);
     af[2] = gemm_lds_read16<2048>(pa);
+    tall_wait_lds5<5>(af[0], bf[0], bf[1], bf[2], bf[3]);  // A0, B0 (the B registers are only named)
+    acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[0]),
+                                                        __builtin_bit_cast(bf16x8, bf[0]), acc[0][0], 0, 0, 0);
     static_for<kTallMI>([&](auto ic) {
       constexpr int i = decltype(ic)::value;
       constexpr int allowed = kTallMI - 1 - i < 2 ? kTallMI - 1 - i : 2;  // younger A reads in flight
       if (i == 0) tall_wait_lds5<allowed>(af[0], bf[0], bf[1], bf[2], bf[3]);
       else tall_wait_lds<allowed>(af[i & 3]);
 #pragma unroll
-      for (int j = 0; j < kTallNJ; ++j)
+      for (int j = (i == 0 ? 1 : 0); j < kTallNJ; ++j)
         acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[i & 3]),
                                                             __builtin_bit_cast(bf16x8, bf[j]), acc[i][j], 0, 0, 0);
       if (i + 3 < kTallMI) af[(i + 3) & 3] = gemm_lds_read16<(i + 3) * 1024>(pa);
+      if (i == 4 && step + kTallStages - 1 < n_steps) {
+        issue(slot_ld);  // step + 3, into the slot of step - 1
+        slot_ld = slot_ld + 1 == kTallStages ? 0 : slot_ld + 1;
+      }
     });
     if (step + 1 < n_steps) {
       // this wave has read everything of this step's slot; the next step has landed once at
-      // most the steps after it (kTallStages - 2 of them were issued) are outstanding
+      // most the steps after it that were issued (up to two) are outstanding
       const int issued_after = n_steps - 2 - step < kTallStages - 2 ? n_steps - 2 - step : kTallStages - 2;
       tall_wait_outstanding(issued_after * n_groups);
       __builtin_amdgcn_s_barrier();  // it is visible; every wave is done with this step's slot
-      if (step + kTallStages < n_steps) {
-        issue(slot_ld);  // into the slot of this step
-        slot_ld = slot_ld + 1 == kTallStages ? 0 : slot_ld + 1;
-      }
       so = so + kTallStageBytes == kTallStages * kTallStageBytes ? 0 : so + kTallStageBytes;
     }
   }
