@@ -126,23 +126,27 @@ __device__ __forceinline__ void swap_halves(uint32_t &a, uint32_t &b) {
 // Output rows: neighbouring q4 of the two lane halves are exchanged so that every lane
 // writes 8 consecutive bf16 values (16 bytes) per store.
 template <bool kUntracked>
+__device__ __forceinline__ void store_out_block(uint16_t *orow, const f32x16 &o, float inv, int g, int mb) {
+#pragma unroll
+  for (int jp = 0; jp < 2; ++jp) {
+    const int e = 8 * jp, od = 8 * jp + 4;  // first register of the even / odd q4 of the pair
+    uint32_t a0 = cvt_pk_bf16(o[e] * inv, o[e + 1] * inv);
+    uint32_t a1 = cvt_pk_bf16(o[e + 2] * inv, o[e + 3] * inv);
+    uint32_t b0 = cvt_pk_bf16(o[od] * inv, o[od + 1] * inv);
+    uint32_t b1 = cvt_pk_bf16(o[od + 2] * inv, o[od + 3] * inv);
+    swap_halves(a0, b0);
+    swap_halves(a1, b1);
+    // lower half: d = 32*mb + 16*jp + 0..7, upper half: the 8 values after those
+    const u32x4 w4 = {a0, a1, b0, b1};
+    if (kUntracked) global_store16_untracked(orow + mb * 32 + 16 * jp + 8 * g, w4);
+    else *reinterpret_cast<u32x4 *>(orow + mb * 32 + 16 * jp + 8 * g) = w4;
+  }
+}
+
+template <bool kUntracked>
 __device__ __forceinline__ void store_out_row(uint16_t *orow, const f32x16 (&o)[4], float inv, int g) {
 #pragma unroll
-  for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-    for (int jp = 0; jp < 2; ++jp) {
-      const int e = 8 * jp, od = 8 * jp + 4;  // first register of the even / odd q4 of the pair
-      uint32_t a0 = cvt_pk_bf16(o[mb][e] * inv, o[mb][e + 1] * inv);
-      uint32_t a1 = cvt_pk_bf16(o[mb][e + 2] * inv, o[mb][e + 3] * inv);
-      uint32_t b0 = cvt_pk_bf16(o[mb][od] * inv, o[mb][od + 1] * inv);
-      uint32_t b1 = cvt_pk_bf16(o[mb][od + 2] * inv, o[mb][od + 3] * inv);
-      swap_halves(a0, b0);
-      swap_halves(a1, b1);
-      // lower half: d = 32*mb + 16*jp + 0..7, upper half: the 8 values after those
-      const u32x4 w4 = {a0, a1, b0, b1};
-      if (kUntracked) global_store16_untracked(orow + mb * 32 + 16 * jp + 8 * g, w4);
-      else *reinterpret_cast<u32x4 *>(orow + mb * 32 + 16 * jp + 8 * g) = w4;
-    }
+  for (int mb = 0; mb < 4; ++mb) store_out_block<kUntracked>(orow, o[mb], inv, g, mb);
 }
 
 // Partial results keep the register layout, so that a wave writes and reads them as
@@ -792,12 +796,14 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnPar
 
 // Finish the units that a range boundary cut: out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s
 // over the pieces s of the unit, always in the order of the pieces.  One wave per (workgroup of
-// the main kernel, group of 32 queries): it reads that workgroup's record, returns at once
-// when it names no unit, and otherwise merges the partials of workgroups w .. w_last with
-// the loads of the next piece in flight while the current one is added.  Lanes map to
-// (query, d) exactly as in the main kernel.
+// the main kernel, group of 32 queries, quarter of the head dimension): it reads that
+// workgroup's record, returns at once when it names no unit, and otherwise merges the partials
+// of workgroups w .. w_last, four pieces at a time with all their loads in flight together.
+// Lanes map to (query, d) exactly as in the main kernel; a wave owns one 32-wide block mb of d.
+constexpr int kCombinePieces = 4;
+
 __global__ __launch_bounds__(kWave) void tree_attn_combine_kernel(AttnParams p) {
-  const int w = blockIdx.x >> 2, dw = blockIdx.x & 3;
+  const int w = blockIdx.x >> 4, dw = (blockIdx.x >> 2) & 3, mb = blockIdx.x & 3;
   const CutRecord cut = *reinterpret_cast<const CutRecord *>(p.cuts + 4 * w);
   if (cut.unit < 0) return;
   const int T = cut.w_last_and_nodes >> 16, w_last = cut.w_last_and_nodes & 0xffff;
@@ -806,44 +812,39 @@ __global__ __launch_bounds__(kWave) void tree_attn_combine_kernel(AttnParams p) 
   const int t = dw * 32 + (lane & 31), g = lane >> 5;
   // lanes beyond the tree read lane 0's data (valid memory) and store nothing
   const int ln = t < T ? lane : 0;
-  auto slot = [&](int wg) { return 2 * (size_t)wg + (wg == w ? 1 : 0); };
-  f32x4 o[2][16];
-  float m[2], l[2];
-  auto fetch = [&](int buf, int wg) {
-    const size_t ps = slot(wg);
-    m[buf] = p.part_ml[part_ml_index(ps, dw, 0, ln)];
-    l[buf] = p.part_ml[part_ml_index(ps, dw, 1, ln)];
+  f32x16 acc;
 #pragma unroll
-    for (int blk = 0; blk < 16; ++blk)
-      o[buf][blk] = *reinterpret_cast<const f32x4 *>(p.part_o + part_o_index(ps, dw, blk, ln));
-  };
-  f32x16 acc[4];
-#pragma unroll
-  for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc[mb][r] = 0.f;
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
   float M = -INFINITY, lsum = 0.f;
-  auto add = [&](int buf) {
-    const float M_new = fmaxf(M, m[buf]);
-    const float M_safe = M_new == -INFINITY ? 0.f : M_new;
-    const float a_old = fast_exp2(M - M_safe), a_new = fast_exp2(m[buf] - M_safe);
-    lsum = lsum * a_old + l[buf] * a_new;
+  for (int w0 = w; w0 <= w_last; w0 += kCombinePieces) {
+    f32x4 o[kCombinePieces][4];
+    float m[kCombinePieces], l[kCombinePieces];
 #pragma unroll
-    for (int blk = 0; blk < 16; ++blk)
+    for (int k = 0; k < kCombinePieces; ++k) {
+      const int wg = w0 + k <= w_last ? w0 + k : w_last;  // past the last piece: re-read it, weight 0
+      const size_t ps = 2 * (size_t)wg + (wg == w ? 1 : 0);
+      m[k] = p.part_ml[part_ml_index(ps, dw, 0, ln)];
+      l[k] = p.part_ml[part_ml_index(ps, dw, 1, ln)];
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
-        acc[blk >> 2][4 * (blk & 3) + j] = acc[blk >> 2][4 * (blk & 3) + j] * a_old + o[buf][blk][j] * a_new;
-    M = M_new;
-  };
-  fetch(0, w);
-  for (int wg = w; wg <= w_last; wg += 2) {
-    if (wg + 1 <= w_last) fetch(1, wg + 1);
-    add(0);
-    if (wg + 2 <= w_last) fetch(0, wg + 2);
-    if (wg + 1 <= w_last) add(1);
+      for (int q4 = 0; q4 < 4; ++q4)
+        o[k][q4] = *reinterpret_cast<const f32x4 *>(p.part_o + part_o_index(ps, dw, 4 * mb + q4, ln));
+    }
+#pragma unroll
+    for (int k = 0; k < kCombinePieces; ++k) {
+      if (w0 + k > w_last) break;  // uniform
+      const float M_new = fmaxf(M, m[k]);
+      const float M_safe = M_new == -INFINITY ? 0.f : M_new;
+      const float a_old = fast_exp2(M - M_safe), a_new = fast_exp2(m[k] - M_safe);
+      lsum = lsum * a_old + l[k] * a_new;
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[4 * q4 + j] = acc[4 * q4 + j] * a_old + o[k][q4][j] * a_new;
+      M = M_new;
+    }
   }
   // the two lanes of an exchange pair hold the same query, so they are active together
-  if (t < T) store_out_row<false>(p.out + ((size_t)cut.unit * p.T_max + t) * kD, acc, 1.f / lsum, g);
+  if (t < T) store_out_block<false>(p.out + ((size_t)cut.unit * p.T_max + t) * kD, acc, 1.f / lsum, g, mb);
 }
 
 // ------------------------------------------------------------------------------------
@@ -963,7 +964,7 @@ static bool launch_bf16(const AttnParams &p, int grid, hipStream_t st) {
   hipLaunchKernelGGL(tree_attn_bf16_kernel<kRingStages>, dim3((unsigned)grid), dim3(kAttnThreads),
                      lds_bytes, st, p);
   if (!launch_ok()) return false;
-  hipLaunchKernelGGL(tree_attn_combine_kernel, dim3((unsigned)grid * 4), dim3(kWave), 0, st, p);
+  hipLaunchKernelGGL(tree_attn_combine_kernel, dim3((unsigned)grid * 16), dim3(kWave), 0, st, p);
   return launch_ok();
 }
 

@@ -351,6 +351,19 @@ def test_prune_without_rank_output_gives_the_same_decisions(pb, oracle):
     assert (u64(res.tree.anc) == ref["anc"]).all()
 
 
+@pytest.mark.parametrize("Hd", [32, 96])
+def test_prune_many_rows_wide_vocabulary_short_rows(pb, oracle, Hd):
+    """616 score rows against a 32000-entry vocabulary: on a 256-unit chip this is the case the
+    352-row tile shape is picked for.  One and three K steps (hidden 32 and 96): the ring's
+    prologue, its drain, and the accumulators read right after a single matrix instruction."""
+    B = 14
+    w = synth.Workload(78, "case", "bf16", B, 1, 128, 128, Hd, 32000, 8, 1e-3)
+    x = synth.make_prune_inputs(w, trees=[synth.rank_product_tree(128, 5)] * B)
+    res, sents = run_prune(pb, x, [x["hidden_states"]])
+    ref, _ = check_prune(oracle, x, res, [x["hidden_states"]], sents)
+    assert 0.1 < ref["n_kept"].sum() / (B * 128) < 0.5
+
+
 # ------------------------------------------------------------------ accept
 
 
