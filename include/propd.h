@@ -184,6 +184,10 @@ PROPD_API propd_status propd_tree_attention(const propd_tree *tree, propd_dtype 
  *              for the probability criterion, two floats per score row and 64 columns.
  * hidden_states and head_weight must be 16-byte aligned for PROPD_BF16
  * (PROPD_ERR_INVALID_ARG otherwise).
+ * The bf16 scoring kernel chooses between two tile shapes on the device, from the number of
+ * score rows.  The environment variable PROPD_HEAD_PLAN (read once per process; for tuning and
+ * tests) overrides the choice: 1 = 256-row tiles, 2 = 352-row tiles; which nodes survive does
+ * not depend on it beyond the order of rounding noted for rank_out.
  */
 #define PROPD_MAX_PAYLOADS 8
 PROPD_API propd_status propd_early_prune(const propd_tree *tree, propd_dtype dt, int32_t hidden,

@@ -209,7 +209,7 @@ __device__ __forceinline__ void tall_epilogue_count(TallAcc &acc, int m0, int v0
             for (int j = 0; j < kTallNJ; ++j) {
               const int col = v0 + wn * WN + 16 * j + c16;
               const float z = acc[i][j][r];
-              cnt += (z > own || (z == own && col < tok)) ? 1 : 0;
+              cnt += (col != tok && (z > own || (z == own && col < tok))) ? 1 : 0;
             }
           }
           packed += cnt << (8 * j4);

@@ -646,7 +646,7 @@ __device__ __forceinline__ void epilogue_count(f32x16 (&acc)[2][FN], int m0, int
             for (int y = 0; y < FN; ++y) {
               const int col = v0 + wn * WN + y * 32 + l32;
               const float z = acc[x][y][r];
-              cnt += (z > own || (z == own && col < tok)) ? 1 : 0;
+              cnt += (col != tok && (z > own || (z == own && col < tok))) ? 1 : 0;
             }
           }
           packed += cnt << (8 * j);
