@@ -129,8 +129,11 @@ PROPD_API propd_status propd_validate_tree(const propd_tree *tree, int32_t *flag
  * where j runs over all L_b = seq_lens[b] cached prefix tokens and over the tree
  * nodes in anc[b,i] (the node's own candidate sequence, itself included).
  *
- *   dt        PROPD_BF16: tensors are bf16, d must be 128; scores, softmax and
+ *   dt        PROPD_BF16: tensors are bf16, d in {64, 128}; scores, softmax and
  *             the output accumulation are fp32, the result is rounded to bf16.
+ *             (d = 128, the head size of every model of Section 5.1, runs the tiled
+ *             matrix-core kernel and needs 16-byte aligned tensors and workspace;
+ *             d = 64 runs a plain one-wave-per-query kernel, without workspace.)
  *             PROPD_F32: tensors are fp32, d in {64, 128}, fp32 throughout.
  *   q, k_tree, v_tree, out   [B,H,T_max,d]
  *   k_cache, v_cache         [B,H,L_max,d]; rows >= L_b are never used

@@ -848,18 +848,27 @@ __global__ __launch_bounds__(kWave) void tree_attn_combine_kernel(AttnParams p) 
 }
 
 // ------------------------------------------------------------------------------------
-// fp32 path: one wave per (sequence, head, node); fp32 loads, products, softmax, output.
+// Plain path: one wave per (sequence, head, node); products, softmax and output sums in fp32.
+// Serves fp32 operands (d = 64 or 128) and bf16 operands with d = 64, the head size the
+// tiled kernel above is not written for; the result is stored in the operands' type.
 // ------------------------------------------------------------------------------------
-struct AttnParamsF32 {
-  const float *q, *k_cache, *v_cache, *k_tree, *v_tree;
-  float *out;
+template <typename E>
+struct AttnParamsPlain {
+  const E *q, *k_cache, *v_cache, *k_tree, *v_tree;
+  E *out;
   const int32_t *seq_lens, *n_nodes;
   const uint64_t *anc;
   int H, T_max, L_max, d;
   float scale;
 };
 
-__global__ __launch_bounds__(kWave) void tree_attn_f32_kernel(AttnParamsF32 p) {
+__device__ __forceinline__ float plain_load(const float *p) { return *p; }
+__device__ __forceinline__ float plain_load(const uint16_t *p) { return bf16_bits_to_f32(*p); }
+__device__ __forceinline__ void plain_store(float *p, float x) { *p = x; }
+__device__ __forceinline__ void plain_store(uint16_t *p, float x) { *p = (uint16_t)f32_to_bf16_bits(x); }
+
+template <typename E>
+__global__ __launch_bounds__(kWave) void tree_attn_plain_kernel(AttnParamsPlain<E> p) {
   const int unit = blockIdx.x / p.T_max, i = blockIdx.x - unit * p.T_max;
   const int b = unit / p.H;
   int L = p.seq_lens[b];
@@ -870,11 +879,11 @@ __global__ __launch_bounds__(kWave) void tree_attn_f32_kernel(AttnParamsF32 p) {
   const int lane = threadIdx.x, d = p.d;
   const uint64_t a_lo = p.anc[((size_t)b * p.T_max + i) * 2];
   const uint64_t a_hi = p.anc[((size_t)b * p.T_max + i) * 2 + 1];
-  const float *q = p.q + ((size_t)unit * p.T_max + i) * d;
-  const float *kc = p.k_cache + (size_t)unit * p.L_max * d;
-  const float *vc = p.v_cache + (size_t)unit * p.L_max * d;
-  const float *kt = p.k_tree + (size_t)unit * p.T_max * d;
-  const float *vt = p.v_tree + (size_t)unit * p.T_max * d;
+  const E *q = p.q + ((size_t)unit * p.T_max + i) * d;
+  const E *kc = p.k_cache + (size_t)unit * p.L_max * d;
+  const E *vc = p.v_cache + (size_t)unit * p.L_max * d;
+  const E *kt = p.k_tree + (size_t)unit * p.T_max * d;
+  const E *vt = p.v_tree + (size_t)unit * p.T_max * d;
 
   float m_run = -INFINITY, l_run = 0.f, o0 = 0.f, o1 = 0.f;  // lane owns columns lane, lane+64
   const int total = L + T;
@@ -885,9 +894,9 @@ __global__ __launch_bounds__(kWave) void tree_attn_f32_kernel(AttnParamsF32 p) {
     const bool ok = in_cache || (j < total && test_bit128(a_lo, a_hi, jt));
     float s = -INFINITY;
     if (ok) {
-      const float *kr = in_cache ? kc + (size_t)j * d : kt + (size_t)jt * d;
+      const E *kr = in_cache ? kc + (size_t)j * d : kt + (size_t)jt * d;
       float acc = 0.f;
-      for (int x = 0; x < d; ++x) acc = fmaf(q[x], kr[x], acc);
+      for (int x = 0; x < d; ++x) acc = fmaf(plain_load(q + x), plain_load(kr + x), acc);
       s = acc * p.scale;
     }
     const float m_new = fmaxf(m_run, wave_reduce_max(s));
@@ -903,14 +912,38 @@ __global__ __launch_bounds__(kWave) void tree_attn_f32_kernel(AttnParamsF32 p) {
       const int src = __ffsll((long long)rest) - 1;
       const float wj = __shfl(w, src, kWave);
       const int jj = j0 + src;
-      const float *vr = jj < L ? vc + (size_t)jj * d : vt + (size_t)(jj - L) * d;
-      if (lane < d) o0 = fmaf(wj, vr[lane], o0);
-      if (lane + 64 < d) o1 = fmaf(wj, vr[lane + 64], o1);
+      const E *vr = jj < L ? vc + (size_t)jj * d : vt + (size_t)(jj - L) * d;
+      if (lane < d) o0 = fmaf(wj, plain_load(vr + lane), o0);
+      if (lane + 64 < d) o1 = fmaf(wj, plain_load(vr + lane + 64), o1);
     }
   }
-  float *o = p.out + ((size_t)unit * p.T_max + i) * d;
-  if (lane < d) o[lane] = o0 / l_run;
-  if (lane + 64 < d) o[lane + 64] = o1 / l_run;
+  E *o = p.out + ((size_t)unit * p.T_max + i) * d;
+  if (lane < d) plain_store(o + lane, o0 / l_run);
+  if (lane + 64 < d) plain_store(o + lane + 64, o1 / l_run);
+}
+
+template <typename E>
+static bool launch_plain(const propd_tree *tree, int H, int d, float scale, const void *q, const void *k_cache,
+                         const void *v_cache, const void *k_tree, const void *v_tree, const int32_t *seq_lens,
+                         int L_max, void *out, hipStream_t st) {
+  AttnParamsPlain<E> p;
+  p.q = reinterpret_cast<const E *>(q);
+  p.k_cache = reinterpret_cast<const E *>(k_cache);
+  p.v_cache = reinterpret_cast<const E *>(v_cache);
+  p.k_tree = reinterpret_cast<const E *>(k_tree);
+  p.v_tree = reinterpret_cast<const E *>(v_tree);
+  p.out = reinterpret_cast<E *>(out);
+  p.seq_lens = seq_lens;
+  p.n_nodes = tree->n_nodes;
+  p.anc = tree->anc;
+  p.H = H;
+  p.T_max = tree->T_max;
+  p.L_max = L_max;
+  p.d = d;
+  p.scale = scale;
+  const long long units = (long long)tree->B * H;
+  hipLaunchKernelGGL(tree_attn_plain_kernel<E>, dim3((unsigned)(units * tree->T_max)), dim3(kWave), 0, st, p);
+  return launch_ok();
 }
 
 // ------------------------------------------------------------------------------------
@@ -990,25 +1023,14 @@ extern "C" propd_status propd_tree_attention(const propd_tree *tree, propd_dtype
 
   if (dt == PROPD_F32) {
     if (d != 64 && d != 128) return PROPD_ERR_UNSUPPORTED;
-    AttnParamsF32 p;
-    p.q = reinterpret_cast<const float *>(q);
-    p.k_cache = reinterpret_cast<const float *>(k_cache);
-    p.v_cache = reinterpret_cast<const float *>(v_cache);
-    p.k_tree = reinterpret_cast<const float *>(k_tree);
-    p.v_tree = reinterpret_cast<const float *>(v_tree);
-    p.out = reinterpret_cast<float *>(out);
-    p.seq_lens = seq_lens;
-    p.n_nodes = tree->n_nodes;
-    p.anc = tree->anc;
-    p.H = H;
-    p.T_max = tree->T_max;
-    p.L_max = L_max;
-    p.d = d;
-    p.scale = scale;
-    hipLaunchKernelGGL(tree_attn_f32_kernel, dim3((unsigned)(units * tree->T_max)), dim3(kWave), 0,
-                       st, p);
-    return launch_ok() ? PROPD_OK : PROPD_ERR_DEVICE;
+    return launch_plain<float>(tree, H, d, scale, q, k_cache, v_cache, k_tree, v_tree, seq_lens, L_max, out, st)
+               ? PROPD_OK
+               : PROPD_ERR_DEVICE;
   }
+  if (d == 64)  // bf16, the smaller head: no workspace is used
+    return launch_plain<uint16_t>(tree, H, d, scale, q, k_cache, v_cache, k_tree, v_tree, seq_lens, L_max, out, st)
+               ? PROPD_OK
+               : PROPD_ERR_DEVICE;
 
   if (d != kD) return PROPD_ERR_UNSUPPORTED;
   // rows are moved 16 bytes per lane, by direct loads to LDS and four-dword loads and stores

@@ -110,6 +110,19 @@ def test_attention_fp32_ragged_d128(pb, oracle):
     check_attention(oracle, x, out, sent)
 
 
+@pytest.mark.parametrize("T_max", [16, 128])
+def test_attention_bf16_head_size_64(pb, oracle, T_max):
+    """bf16 tensors with the smaller head size (the plain kernel, no workspace): ragged
+    lengths, an empty cache, a one-node tree, trees smaller than the slot."""
+    rng = np.random.default_rng(64 + T_max)
+    shapes = [synth.rank_product_tree(T_max, 3 if T_max == 16 else 5),
+              synth.random_tree(rng, max(1, T_max // 3)), synth.chain_tree(1)]
+    w = synth.Workload(82, "case", "bf16", 3, 2, 64, T_max, 0, 0, 0, 1e-3)
+    x = synth.make_attention_inputs(w, seq_lens=np.array([131, 0, 64], np.int32), trees=shapes)
+    out, sent = run_attention(pb, x)
+    check_attention(oracle, x, out, sent)
+
+
 @pytest.mark.parametrize("T_max,kind", [(16, "rank"), (32, "random"), (64, "rank"), (128, "rank"),
                                         (128, "chain"), (96, "random")])
 def test_attention_bf16_tree_sizes(pb, oracle, T_max, kind):
