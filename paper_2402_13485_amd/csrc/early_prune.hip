@@ -40,13 +40,9 @@ namespace propd {
 // scratch layout
 // ------------------------------------------------------------------------------------
 struct PruneScratch {
-  int32_t *n_par;       // [B]        nodes with children
-  int32_t *local_list;  // [B*T_max]  per sequence: nodes with children, ascending
   int32_t *row_src;     // [B*T_max]  score row -> b*T_max + node
-  int32_t *row_base;    // [B+1]      exclusive prefix of n_par; [B] = total rows
+  int32_t *row_base;    // [B+1]      score rows of the sequences before b; [B] = total rows
   int32_t *row_info;    // [B*T_max][2] score row -> (first position in child_list, children)
-  int32_t *child_pos;   // [B*T_max]  node -> first position of its children in child_list
-  int32_t *child_cnt;   // [B*T_max]  node -> number of children
   int32_t *child_list;  // [B*T_max]  b*T_max + child, grouped by parent, per sequence slot
   float *own;           // [B*T_max]  z_parent[token] of every non-root node
   float *logq;          // [B*T_max]  probability criterion: log q of every node's token
@@ -66,13 +62,9 @@ static PruneScratch carve_scratch(void *base, int B, int T_max, int vocab) {
     off += align_up(bytes, 256);
     return q;
   };
-  s.n_par = reinterpret_cast<int32_t *>(take((size_t)B * 4));
-  s.local_list = reinterpret_cast<int32_t *>(take(nt * 4));
   s.row_src = reinterpret_cast<int32_t *>(take(nt * 4));
   s.row_base = reinterpret_cast<int32_t *>(take((size_t)(B + 1) * 4));
   s.row_info = reinterpret_cast<int32_t *>(take(nt * 8));
-  s.child_pos = reinterpret_cast<int32_t *>(take(nt * 4));
-  s.child_cnt = reinterpret_cast<int32_t *>(take(nt * 4));
   s.child_list = reinterpret_cast<int32_t *>(take(nt * 4));
   s.own = reinterpret_cast<float *>(take(nt * 4));
   s.logq = reinterpret_cast<float *>(take(nt * 4));
@@ -135,36 +127,83 @@ __global__ __launch_bounds__(kScanThreads) void cu_nodes_kernel(int B,
 }
 
 // ------------------------------------------------------------------------------------
-// preparation: tables (workgroup 0) and the children's own scores (the other workgroups)
+// preparation: tables (the first workgroups) and the children's own scores (the others)
 // ------------------------------------------------------------------------------------
 struct PrepareArgs {
   int B, T_max, hidden, vocab;
   const int32_t *n_nodes, *parent, *token;
   const void *hidden_states, *head_weight;
-  int32_t *n_par, *local_list, *row_src, *row_base, *row_info, *child_pos, *child_cnt, *child_list;
+  int32_t *row_src, *row_base, *row_info, *child_list;
   float *own;
 };
 
-// One wave per sequence at a time, two nodes per lane (lane and lane + 64); everything a wave
-// needs from other lanes goes through a 128-entry array of its own in LDS, ordered by the
-// wave's own program order (LDS operations of a wave complete in order).
+constexpr int kTableWaves = kScanThreads / kWave;  // sequences per table workgroup, one per wave
+
+// Everything a wave needs from other lanes goes through a 128-entry array of its own in LDS,
+// ordered by the wave's own program order (LDS operations of a wave complete in order).
 __device__ __forceinline__ void wave_lds_fence() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
-__device__ void prepare_tables(const PrepareArgs &a) {
-  __shared__ int s_cnt[kScanThreads / kWave][PROPD_MAX_TREE];
+// The valid parent of node `nd` of a tree with T nodes as loaded (-1: none; a parent that is no
+// earlier node makes no edge).
+__device__ __forceinline__ int valid_parent(int nd, int T, int p) {
+  return (nd > 0 && nd < T && p >= 0 && p < nd) ? p : -1;
+}
+
+// Table workgroup g, wave wv: the tables of sequence b = kTableWaves * g + wv, two nodes per lane
+// (lane and lane + 64).  A sequence's score rows follow those of all sequences before it, so the
+// wave needs the number of nodes with children of every earlier sequence: the waves of the
+// workgroup count them together (sequence x by wave x % kTableWaves, a mark per parent in LDS,
+// all loads of a wave's sequences in flight before the first is used) and exchange the counts
+// through LDS.  No workgroup waits for another: each one counts for itself what it needs.
+__device__ void prepare_tables(const PrepareArgs &a, int g) {
+  constexpr int kBatch = 8;  // sequences a wave counts per round
+  __shared__ int s_cnt[kTableWaves][PROPD_MAX_TREE];
+  __shared__ int s_rows[kTableWaves];  // score rows before this workgroup's sequences, per counting wave
+  __shared__ int s_own[kTableWaves];   // nodes with children of the workgroup's own sequences
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   int *cnt = s_cnt[wv];
-  for (int b = wv; b < a.B; b += kScanThreads / kWave) {
-    const int T = clamp_tree(a.n_nodes[b], a.T_max);
-    const size_t base = (size_t)b * a.T_max;
-    int node[2] = {lane, lane + 64}, par[2], slot[2];
+  const int b = kTableWaves * g + wv;
+  const int node[2] = {lane, lane + 64};
+
+  // ---- nodes with children of the earlier sequences this wave counts: x = wv, wv + 4, ... < 4 g
+  int rows_before = 0;
+  for (int x0 = wv; x0 < kTableWaves * g; x0 += kTableWaves * kBatch) {
+    int Tx[kBatch], px[kBatch][2];
+#pragma unroll
+    for (int i = 0; i < kBatch; ++i) {
+      const int x = x0 + kTableWaves * i;
+      const bool in = x < kTableWaves * g;
+      const size_t base = (size_t)(in ? x : 0) * a.T_max;
+      Tx[i] = in ? clamp_tree(a.n_nodes[x], a.T_max) : 0;
+#pragma unroll
+      for (int h = 0; h < 2; ++h) px[i][h] = node[h] < a.T_max ? a.parent[base + node[h]] : -1;
+    }
+#pragma unroll
+    for (int i = 0; i < kBatch; ++i) {
+      if (x0 + kTableWaves * i >= kTableWaves * g) break;  // uniform
+      cnt[node[0]] = 0;
+      cnt[node[1]] = 0;
+      wave_lds_fence();
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int p = valid_parent(node[h], Tx[i], px[i][h]);
+        if (p >= 0) cnt[p] = 1;
+      }
+      wave_lds_fence();
+      rows_before += __popcll(__ballot(cnt[node[0]] != 0)) + __popcll(__ballot(cnt[node[1]] != 0));
+      wave_lds_fence();
+    }
+  }
+
+  // ---- this wave's own sequence
+  int T = 0, par[2] = {-1, -1}, slot[2] = {0, 0}, mine[2] = {0, 0}, incl[2] = {0, 0}, par_before[2] = {0, 0};
+  int run_par = 0;
+  const size_t base = (size_t)(b < a.B ? b : 0) * a.T_max;
+  if (b < a.B) {  // uniform over the wave
+    T = clamp_tree(a.n_nodes[b], a.T_max);
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      par[h] = -1;
-      if (node[h] > 0 && node[h] < T) {
-        const int p = a.parent[base + node[h]];
-        par[h] = (p >= 0 && p < node[h]) ? p : -1;  // a parent that is no earlier node: no edge
-      }
+      par[h] = valid_parent(node[h], T, node[h] < a.T_max ? a.parent[base + node[h]] : -1);
       cnt[node[h]] = 0;
     }
     wave_lds_fence();
@@ -172,12 +211,11 @@ __device__ void prepare_tables(const PrepareArgs &a) {
 #pragma unroll
     for (int h = 0; h < 2; ++h) slot[h] = par[h] >= 0 ? atomicAdd(&cnt[par[h]], 1) : 0;
     wave_lds_fence();
-    int mine[2] = {cnt[node[0]], cnt[node[1]]};
+    mine[0] = cnt[node[0]];
+    mine[1] = cnt[node[1]];
     wave_lds_fence();
     // exclusive prefix of the child counts over the nodes, and of "has children"
-    int incl[2], par_before[2];
-    uint64_t has[2];
-    int run = 0, run_par = 0;
+    int run = 0;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       incl[h] = mine[h];
@@ -189,42 +227,38 @@ __device__ void prepare_tables(const PrepareArgs &a) {
       const int total = __shfl(incl[h], 63, kWave);
       incl[h] += run;
       run += total;
-      has[h] = __ballot(mine[h] > 0);
-      par_before[h] = run_par + __popcll(has[h] & ((1ull << lane) - 1ull));
-      run_par += __popcll(has[h]);
+      const uint64_t has = __ballot(mine[h] > 0);
+      par_before[h] = run_par + __popcll(has & ((1ull << lane) - 1ull));
+      run_par += __popcll(has);
     }
-    // positions are global: b*T_max + position in the sequence's slot
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      cnt[node[h]] = incl[h] - mine[h];  // first position of this node's children
-    }
+    for (int h = 0; h < 2; ++h) cnt[node[h]] = incl[h] - mine[h];  // first position of this node's children
     wave_lds_fence();
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      if (node[h] < a.T_max) {
-        a.child_pos[base + node[h]] = (int)base + incl[h] - mine[h];
-        a.child_cnt[base + node[h]] = mine[h];
-      }
+    for (int h = 0; h < 2; ++h)
       if (par[h] >= 0) a.child_list[base + cnt[par[h]] + slot[h]] = (int)base + node[h];
-      if (mine[h] > 0) a.local_list[base + par_before[h]] = node[h];
-    }
-    if (lane == 0) a.n_par[b] = run_par;
-    wave_lds_fence();
   }
-  __threadfence_block();
+  if (lane == 0) {
+    s_rows[wv] = rows_before;
+    s_own[wv] = run_par;
+  }
   __syncthreads();
-  block_exclusive_scan(a.n_par, a.row_base, a.B);
-  __threadfence_block();
-  __syncthreads();
-  for (int b = wv; b < a.B; b += kScanThreads / kWave) {
-    const size_t base = (size_t)b * a.T_max;
-    const int n = a.n_par[b], first = a.row_base[b];
-    for (int r = lane; r < n; r += kWave) {
-      const int nd = a.local_list[base + r];
-      a.row_src[first + r] = (int)base + nd;
-      a.row_info[2 * (first + r)] = a.child_pos[base + nd];
-      a.row_info[2 * (first + r) + 1] = a.child_cnt[base + nd];
+  if (b >= a.B) return;
+  int first = 0;
+#pragma unroll
+  for (int w = 0; w < kTableWaves; ++w) first += s_rows[w] + (w < wv ? s_own[w] : 0);
+  // positions are global: b*T_max + position in the sequence's slot
+#pragma unroll
+  for (int h = 0; h < 2; ++h)
+    if (mine[h] > 0) {
+      const int r = first + par_before[h];
+      a.row_src[r] = (int)base + node[h];
+      a.row_info[2 * r] = (int)base + incl[h] - mine[h];
+      a.row_info[2 * r + 1] = mine[h];
     }
+  if (lane == 0) {
+    a.row_base[b] = first;
+    if (b == a.B - 1) a.row_base[a.B] = first + run_par;
   }
 }
 
@@ -287,12 +321,23 @@ __device__ void own_scores_bf16(const PrepareArgs &a, int b, int group) {
       __syncthreads();  // the step is in LDS; wave 0 is done with the other buffer
       if (wave == 0) {
         const int k16_left = n_k16 - step * (kOwnStep / 16);
+        if (k16_left >= kOwnStep / 16) {
+          // a whole step: no condition between the reads, so that all of them are in flight
+          // before the first product needs its pair
 #pragma unroll
-        for (int ks = 0; ks < kOwnStep / 16; ++ks) {
-          if (ks < k16_left) {
+          for (int ks = 0; ks < kOwnStep / 16; ++ks) {
             const bf16x8 fa = *reinterpret_cast<const bf16x8 *>(buf_a + frag_off + ks * 32);
             const bf16x8 fb = *reinterpret_cast<const bf16x8 *>(buf_b + frag_off + ks * 32);
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc, 0, 0, 0);
+          }
+        } else {
+#pragma unroll
+          for (int ks = 0; ks < kOwnStep / 16; ++ks) {
+            if (ks < k16_left) {
+              const bf16x8 fa = *reinterpret_cast<const bf16x8 *>(buf_a + frag_off + ks * 32);
+              const bf16x8 fb = *reinterpret_cast<const bf16x8 *>(buf_b + frag_off + ks * 32);
+              acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc, 0, 0, 0);
+            }
           }
         }
       }
@@ -330,12 +375,14 @@ __device__ void own_scores_f32(const PrepareArgs &a, int b, int group) {
 
 template <bool kBf16>
 __global__ __launch_bounds__(kScanThreads) void prune_prepare_kernel(PrepareArgs a) {
-  if (blockIdx.x == 0) {
-    prepare_tables(a);
+  const int table_groups = (a.B + kTableWaves - 1) / kTableWaves;
+  if ((int)blockIdx.x < table_groups) {
+    prepare_tables(a, blockIdx.x);
     return;
   }
   const int groups = (a.T_max + kOwnNodes - 1) / kOwnNodes;
-  const int b = (blockIdx.x - 1) / groups, group = (blockIdx.x - 1) - b * groups;
+  const int ob = blockIdx.x - table_groups;
+  const int b = ob / groups, group = ob - b * groups;
   if (kBf16) own_scores_bf16(a, b, group);
   else own_scores_f32(a, b, group);
 }
@@ -1382,16 +1429,13 @@ static propd_status prune_impl(
     pr.token = tree->token;
     pr.hidden_states = hidden_states;
     pr.head_weight = head_weight;
-    pr.n_par = ws.n_par;
-    pr.local_list = ws.local_list;
     pr.row_src = ws.row_src;
     pr.row_base = ws.row_base;
     pr.row_info = ws.row_info;
-    pr.child_pos = ws.child_pos;
-    pr.child_cnt = ws.child_cnt;
     pr.child_list = ws.child_list;
     pr.own = ws.own;
-    const unsigned prep_grid = 1u + (unsigned)B * (unsigned)((T_max + kOwnNodes - 1) / kOwnNodes);
+    const unsigned prep_grid = (unsigned)((B + kTableWaves - 1) / kTableWaves) +
+                               (unsigned)B * (unsigned)((T_max + kOwnNodes - 1) / kOwnNodes);
     if (dt == PROPD_BF16)
       hipLaunchKernelGGL(prune_prepare_kernel<true>, dim3(prep_grid), dim3(kScanThreads), 0, st, pr);
     else

@@ -377,6 +377,21 @@ def test_prune_many_rows_wide_vocabulary_short_rows(pb, oracle, Hd):
     assert 0.1 < ref["n_kept"].sum() / (B * 128) < 0.5
 
 
+def test_prune_many_sequences_of_mixed_shapes(pb, oracle):
+    """70 sequences: a sequence's score rows follow those of all sequences before it, counted
+    by the table workgroups four sequences at a time, more than one round of counting for the
+    last ones; chains, one-node trees and bushy trees in turn, so the counts differ."""
+    B, T_max = 70, 16
+    rng = np.random.default_rng(70)
+    kinds = [lambda: synth.rank_product_tree(16, 3), lambda: synth.chain_tree(1),
+             lambda: synth.random_tree(rng, int(rng.integers(2, 17))), lambda: synth.chain_tree(9)]
+    shapes = [kinds[i % 4]() for i in range(B)]
+    w = synth.Workload(77, "case", "bf16", B, 1, 128, T_max, 64, 700, 5, 1e-3)
+    x = synth.make_prune_inputs(w, trees=shapes)
+    res, sents = run_prune(pb, x, [x["hidden_states"]])
+    check_prune(oracle, x, res, [x["hidden_states"]], sents)
+
+
 # ------------------------------------------------------------------ accept
 
 
