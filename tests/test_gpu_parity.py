@@ -377,6 +377,56 @@ def test_prune_many_rows_wide_vocabulary_short_rows(pb, oracle, Hd):
     assert 0.1 < ref["n_kept"].sum() / (B * 128) < 0.5
 
 
+@pytest.mark.parametrize("dtype,B,T_max,Hd,V", [("bf16", 3, 64, 256, 4096), ("bf16", 14, 128, 96, 32000),
+                                                ("f32", 2, 32, 64, 700)])
+def test_prune_equal_scores_rank_by_token_id(pb, oracle, dtype, B, T_max, Hd, V):
+    """Vocabulary entries with identical weight rows score identically under every parent, in
+    any arithmetic.  Two siblings that carry such a pair must be ranked next to each other, the
+    lower id first: the score a child is compared against and the score the kernel computes
+    for the same entry in another place have to be the same bits for that.  Both tile shapes of
+    the bf16 kernel (few rows; 616 rows against a wide vocabulary) and the fp32 kernel; the
+    twin entry lies in the same column tile or in a distant one."""
+    rng = np.random.default_rng(B * 1000 + Hd)
+    depth = {32: 4, 64: 4, 128: 5}[T_max]
+    shapes = [synth.rank_product_tree(T_max, depth)] * B
+    n_nodes, parent, _ = synth.pad_trees(shapes, T_max)
+    token = synth.draw_tokens(rng, n_nodes, parent, V)
+    if dtype == "bf16":
+        hidden = synth.normal_bf16(rng, (B, T_max, Hd))
+        weight = synth.normal_bf16(rng, (V, Hd), sigma=0.05)
+    else:
+        hidden = synth.normal_f32(rng, (B, T_max, Hd))
+        weight = synth.normal_f32(rng, (V, Hd), 0.05)
+    used = set(int(t) for t in token[token >= 0])
+    pairs = []
+    for b in range(B):
+        kids = synth.children_lists(parent[b], int(n_nodes[b]))
+        for p_, ks in enumerate(kids):
+            if len(ks) < 2:
+                continue
+            c1, c2 = ks[0], ks[1]
+            t1 = int(token[b, c1])
+            t2 = (t1 + (1 if len(pairs) % 2 else 300)) % V
+            if t2 in used or t2 == t1:
+                continue
+            used.add(t2)
+            weight[t2] = weight[t1]
+            token[b, c2] = t2
+            pairs.append((b, c1, c2, t1, t2))
+    assert len(pairs) >= 4 * B
+    k = 8
+    x = dict(n_nodes=n_nodes, parent=parent, token=token, hidden_states=hidden, head_weight=weight, top_k=k)
+    res, _ = run_prune(pb, x)
+    rank = to_host(res.rank)
+    rank_ref, _ = oracle.early_head_rank(n_nodes, parent, token, hidden, weight, k)
+    for b, c1, c2, t1, t2 in pairs:
+        lo, hi = (c1, c2) if t1 < t2 else (c2, c1)
+        assert rank_ref[b, hi] == rank_ref[b, lo] + 1
+        assert rank[b, hi] == rank[b, lo] + 1, (b, c1, c2, t1, t2, rank[b, c1], rank[b, c2])
+    valid = rank_ref >= 0
+    assert np.abs(rank - rank_ref)[valid].max() <= 3
+
+
 def test_prune_many_sequences_of_mixed_shapes(pb, oracle):
     """70 sequences: a sequence's score rows follow those of all sequences before it, counted
     by the table workgroups four sequences at a time, more than one round of counting for the
