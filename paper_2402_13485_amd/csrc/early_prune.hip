@@ -266,11 +266,12 @@ __device__ void prepare_tables(const PrepareArgs &a, int g) {
 // sequence b (few nodes per workgroup: the rows are fetched once, from all over the weight
 // matrix, and it is the number of workgroups that brings the bytes in flight).  Tile rows:
 // A row j = hidden state of the parent of node j, B row j = weight row of node j's token; the
-// diagonal of A . B^T holds the scores wanted (rows 8..31 of the 32-row tile repeat rows
+// diagonal of A . B^T holds the scores wanted (rows 8..15 of the 16-row tile repeat rows
 // 0..7).  All four waves fetch (coalesced, eight 256-deep steps ahead, through registers into
-// a padded double buffer in LDS); wave 0 runs the chain of 32x32x16 matrix instructions over
-// K in rising order, starting from zero: the chain the scoring kernel runs for every element
-// of its tiles.
+// a padded double buffer in LDS); wave 0 runs the chain of 16x16x32 matrix instructions over
+// K in rising order, starting from zero: the chain the 352-row tiles of the scoring kernel run
+// for every element (the 32x32x16 chain of the 256-row tiles, two instructions per 32 of K,
+// gives the same bits: measured, and held to it by the test of equal scores on both shapes).
 constexpr int kOwnNodes = 8;                      // children per workgroup
 constexpr int kOwnStep = 256;                     // K per fetch step
 constexpr int kOwnRowBytes = kOwnStep * 2 + 16;   // padded: the 8 rows start 4 banks apart
@@ -294,7 +295,7 @@ __device__ void own_scores_bf16(const PrepareArgs &a, int b, int group) {
   const uint16_t *a_src = reinterpret_cast<const uint16_t *>(a.hidden_states) + (base + p) * (size_t)a.hidden + ld_piece * 8;
   const uint16_t *b_src = reinterpret_cast<const uint16_t *>(a.head_weight) + (size_t)tk * a.hidden + ld_piece * 8;
   const int n_steps = (a.hidden + kOwnStep - 1) / kOwnStep;
-  const int n_k16 = a.hidden / 16;
+  const int n_k32 = a.hidden / 32;
   u32x4 ra[kOwnAhead], rb[kOwnAhead];
   auto fetch = [&](int slot, int step) {
     const bool in = step < n_steps && step * kOwnStep + ld_piece * 8 < a.hidden;
@@ -304,11 +305,11 @@ __device__ void own_scores_bf16(const PrepareArgs &a, int b, int group) {
   };
 #pragma unroll
   for (int i = 0; i < kOwnAhead; ++i) fetch(i, i);
-  f32x16 acc;
-#pragma unroll
-  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-  const int l32 = lane & 31, g = lane >> 5;
-  const int frag_off = (l32 & (kOwnNodes - 1)) * kOwnRowBytes + g * 16;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  // fragment of the 16x16x32 instruction: lane -> row lane % 16 (rows 8..15 repeat rows 0..7),
+  // 8 consecutive k from 8 * (lane / 16)
+  const int c16 = lane & 15, kq = lane >> 4;
+  const int frag_off = (c16 & (kOwnNodes - 1)) * kOwnRowBytes + kq * 16;
   for (int s0 = 0; s0 < n_steps; s0 += kOwnAhead) {
 #pragma unroll
     for (int i = 0; i < kOwnAhead; ++i) {
@@ -320,23 +321,23 @@ __device__ void own_scores_bf16(const PrepareArgs &a, int b, int group) {
       fetch(i, step + kOwnAhead);
       __syncthreads();  // the step is in LDS; wave 0 is done with the other buffer
       if (wave == 0) {
-        const int k16_left = n_k16 - step * (kOwnStep / 16);
-        if (k16_left >= kOwnStep / 16) {
+        const int k32_left = n_k32 - step * (kOwnStep / 32);
+        if (k32_left >= kOwnStep / 32) {
           // a whole step: no condition between the reads, so that all of them are in flight
           // before the first product needs its pair
 #pragma unroll
-          for (int ks = 0; ks < kOwnStep / 16; ++ks) {
-            const bf16x8 fa = *reinterpret_cast<const bf16x8 *>(buf_a + frag_off + ks * 32);
-            const bf16x8 fb = *reinterpret_cast<const bf16x8 *>(buf_b + frag_off + ks * 32);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc, 0, 0, 0);
+          for (int ks = 0; ks < kOwnStep / 32; ++ks) {
+            const bf16x8 fa = *reinterpret_cast<const bf16x8 *>(buf_a + frag_off + ks * 64);
+            const bf16x8 fb = *reinterpret_cast<const bf16x8 *>(buf_b + frag_off + ks * 64);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fb, acc, 0, 0, 0);
           }
         } else {
 #pragma unroll
-          for (int ks = 0; ks < kOwnStep / 16; ++ks) {
-            if (ks < k16_left) {
-              const bf16x8 fa = *reinterpret_cast<const bf16x8 *>(buf_a + frag_off + ks * 32);
-              const bf16x8 fb = *reinterpret_cast<const bf16x8 *>(buf_b + frag_off + ks * 32);
-              acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc, 0, 0, 0);
+          for (int ks = 0; ks < kOwnStep / 32; ++ks) {
+            if (ks < k32_left) {
+              const bf16x8 fa = *reinterpret_cast<const bf16x8 *>(buf_a + frag_off + ks * 64);
+              const bf16x8 fb = *reinterpret_cast<const bf16x8 *>(buf_b + frag_off + ks * 64);
+              acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fb, acc, 0, 0, 0);
             }
           }
         }
@@ -345,15 +346,14 @@ __device__ void own_scores_bf16(const PrepareArgs &a, int b, int group) {
   }
   if (wave != 0) return;
   mfma_settle();
-  // element (row, col) of the tile sits in lane col + 32*g, register r, with
-  // row = 8*(r/4) + 4*g + r%4: the diagonal element of column j < 8 is in the half
-  // g = j >> 2, register j & 3
+  // element (row, col) of the tile sits in lane col + 16 * (row / 4), register row % 4: the
+  // diagonal element of column j < 8 is in the lane quarter j >> 2, register j & 3
   float diag = 0.f;
 #pragma unroll
   for (int r = 0; r < 4; ++r)
-    if (r == (l32 & 3)) diag = acc[r];
-  const int my_node = kOwnNodes * group + l32;
-  if (l32 < kOwnNodes && g == (l32 >> 2) && my_node > 0 && my_node < T) a.own[base + my_node] = diag;
+    if (r == (c16 & 3)) diag = acc[r];
+  const int my_node = kOwnNodes * group + c16;
+  if (c16 < kOwnNodes && kq == (c16 >> 2) && my_node > 0 && my_node < T) a.own[base + my_node] = diag;
 }
 
 // fp32: one lane per node, the same sequential fused multiply-add chain as the scoring kernel
