@@ -1093,9 +1093,19 @@ __global__ __launch_bounds__(PROPD_MAX_TREE * kCompactSplit) void prune_compact_
     int32_t *__restrict__ out_token, int32_t *__restrict__ out_depth,
     uint64_t *__restrict__ out_anc, int32_t *__restrict__ rank_out) {
   const int b = blockIdx.x, i = threadIdx.x & (PROPD_MAX_TREE - 1), q = threadIdx.x / PROPD_MAX_TREE;
-  const int T = clamp_tree(n_nodes[b], T_max);
   const size_t base = (size_t)b * T_max;
-  const bool valid = i < T;
+  // Everything this thread reads is requested before the first value is used: the tree size,
+  // the tile count and the node's own words do not wait for each other.  Slots past the tree
+  // are read too (they exist) and dropped.
+  const bool slot = i < T_max, worker = q == 0;
+  const int T_raw = n_nodes[b];
+  uint64_t a_lo = 0, a_hi = 0;
+  int my_token = -1;
+  if (worker && slot) {
+    a_lo = anc[(base + i) * 2];
+    a_hi = anc[(base + i) * 2 + 1];
+    my_token = token[base + i];
+  }
   __shared__ uint64_t s_fail[2], s_keep[2];
   __shared__ float s_q[PROPD_MAX_TREE], s_lm[PROPD_MAX_TREE];
   __shared__ int s_sum[kCompactSplit][PROPD_MAX_TREE];
@@ -1112,10 +1122,10 @@ __global__ __launch_bounds__(PROPD_MAX_TREE * kCompactSplit) void prune_compact_
       }
     }
     int sum = 0;
-    if (valid && i > 0) {
+    if (slot && i > 0) {
       const int32_t *src = cnt_part + base + i;
       const size_t stride = (size_t)B * T_max;
-      constexpr int kInFlight = 8;
+      constexpr int kInFlight = 32;
       for (int t0 = q; t0 < n_tiles; t0 += kCompactSplit * kInFlight) {
         int v[kInFlight];
 #pragma unroll
@@ -1129,16 +1139,14 @@ __global__ __launch_bounds__(PROPD_MAX_TREE * kCompactSplit) void prune_compact_
     }
     s_sum[q][i] = sum;
   }
+  const int T = clamp_tree(T_raw, T_max);
+  const bool valid = i < T;
+  if (!valid) {
+    a_lo = a_hi = 0;
+    my_token = -1;
+  }
   __syncthreads();
   // from here on one thread per node does the work; the others only meet it at the barriers
-  const bool worker = q == 0;
-  uint64_t a_lo = 0, a_hi = 0;
-  int my_token = -1;
-  if (worker && valid) {
-    a_lo = anc[(base + i) * 2];
-    a_hi = anc[(base + i) * 2 + 1];
-    my_token = token[base + i];
-  }
   bool fail = false;
   if (crit.kind == 0) {
     if (worker) {
