@@ -55,7 +55,7 @@ def build_inputs(w, synth):
     return att, pr, acc, token
 
 
-def resident_step(w, att, pr, acc, token, torch, pb):
+def resident_step(w, att, pr, acc, token, torch, pb, rotate_kv=False):
     """Uploads one workload's inputs (they stay resident) and returns a namespace holding
     `step(marks=None)`, one pass of the hot path, and the tensors it works on."""
     import types
@@ -68,6 +68,14 @@ def resident_step(w, att, pr, acc, token, torch, pb):
     depth, anc = pb.propd_tree_mask(nn, par)
     tree = pb.Tree(n_nodes=nn, parent=par, token=to_dev(token), depth=depth, anc=anc)
     q, kc, vc = to_dev(att["q"]), to_dev(att["k_cache"]), to_dev(att["v_cache"])
+    # A K/V cache smaller than the chip's 256 MB last-level cache is served from that cache
+    # step after step; with rotate_kv such a workload rotates among enough copies of it (at
+    # distinct addresses) that every attention call streams its K/V from HBM.
+    kv_bytes_resident = kc.numel() * kc.element_size() * 2
+    n_kv_copies = 1 if (kv_bytes_resident >= (1 << 30) or not rotate_kv) else \
+        min(64, -(-(3 << 28) // kv_bytes_resident))
+    kv_copies = [(kc, vc)] + [(kc.clone(), vc.clone()) for _ in range(n_kv_copies - 1)]
+    kv_turn = [0]
     kt, vt = to_dev(att["k_tree"]), to_dev(att["v_tree"])
     seq = to_dev(att["seq_lens"])
     out_full = torch.empty_like(q)
@@ -103,15 +111,18 @@ def resident_step(w, att, pr, acc, token, torch, pb):
     def step(marks=None):
         """One pass of the hot path; `marks` collects events around the parts."""
         m = [ev() for _ in range(5)] if marks is not None else None
+        kc_a, vc_a = kv_copies[kv_turn[0] % n_kv_copies]
+        kc_b, vc_b = kv_copies[(kv_turn[0] + 1) % n_kv_copies]
+        kv_turn[0] += 2
         if m: m[0].record()
-        pb.propd_tree_attention(tree, q, kc, vc, kt, vt, seq, att["scale"], out=out_full,
+        pb.propd_tree_attention(tree, q, kc_a, vc_a, kt, vt, seq, att["scale"], out=out_full,
                                 workspace=ws_att)
         if m: m[1].record()
         if prune:
             res = pb.propd_early_prune(tree, hid, hw, w.top_k, payloads=payloads,
                                        payload_out=payload_out, workspace=ws_pr)
             if m: m[2].record()
-            pb.propd_tree_attention(res.tree, payload_out[1], kc, vc, payload_out[2],
+            pb.propd_tree_attention(res.tree, payload_out[1], kc_b, vc_b, payload_out[2],
                                     payload_out[3], seq, att["scale"], out=out_small,
                                     workspace=ws_att)
             t_acc = res.tree
@@ -135,6 +146,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", type=int, default=4, choices=[2, 3, 4, 5])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--rotate-kv", action="store_true",
+                    help="workloads whose K/V cache fits the 256 MB last-level cache (C2, C3): rotate among "
+                         "enough copies of it that every attention call streams from HBM")
     ap.add_argument("--cpu-seconds", type=float, default=10.0,
                     help="CPU work the oracle baseline is bounded to (whole sequences)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -174,7 +188,7 @@ def main() -> int:
     if args.layers > 0:
         return multi_layer_table(w, args, torch, pb, synth)
     att, pr, acc, token = build_inputs(w, synth)
-    S = resident_step(w, att, pr, acc, token, torch, pb)
+    S = resident_step(w, att, pr, acc, token, torch, pb, rotate_kv=args.rotate_kv)
     B, H, d, T_max, L_max = S.B, S.H, S.d, S.T_max, S.L_max
     step, prune, seq, kc, vc, kt, vt, tree, ev = S.step, S.prune, S.seq, S.kc, S.vc, S.kt, S.vt, S.tree, S.ev
     n_kept_host = S.n_kept_host
@@ -251,7 +265,8 @@ def main() -> int:
                    "sum_L": int(att["seq_lens"].sum()), "sum_T": sum_T, "hidden": w.hidden,
                    "vocab": w.vocab, "top_k": w.top_k,
                    "survivors": int(np.sum(n_kept_host)),
-                   "mean_accept_len": float(accept_len.mean())},
+                   "mean_accept_len": float(accept_len.mean()),
+                   "kv_cache_copies_rotated": int(S.n_kv_copies)},
         "step_us": pct(step_ms_events),
         "parts_us": {"attention_full_tree": att_full_ms * 1e3, "early_prune": prune_ms * 1e3,
                      "attention_compacted_tree": att_small_ms * 1e3, "accept": accept_ms * 1e3,
