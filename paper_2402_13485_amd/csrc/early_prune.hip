@@ -468,17 +468,18 @@ __device__ __forceinline__ void gemm_wait_vmem() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-// Waits until at most n of this wave's loads are outstanding (n = whole steps of 3 or 4 loads).
-__device__ __forceinline__ void gemm_wait_outstanding(int n) {
-  if (n >= 16) gemm_wait_vmem<16>();
-  else if (n >= 12) gemm_wait_vmem<12>();
-  else if (n >= 9) gemm_wait_vmem<9>();
-  else if (n >= 8) gemm_wait_vmem<8>();
-  else if (n >= 6) gemm_wait_vmem<6>();
-  else if (n >= 4) gemm_wait_vmem<4>();
-  else if (n >= 3) gemm_wait_vmem<3>();
-  else gemm_wait_vmem<0>();
+template <int N>
+__device__ __forceinline__ void gemm_wait_at_most(int n) {
+  if constexpr (N == 0) {
+    gemm_wait_vmem<0>();
+  } else {
+    if (n >= N) gemm_wait_vmem<N>();
+    else gemm_wait_at_most<N - 1>(n);
+  }
 }
+// Waits until at most n <= MAXN of this wave's loads are outstanding (n = whole steps of 1 to 4 loads).
+template <int MAXN>
+__device__ __forceinline__ void gemm_wait_outstanding(int n) { gemm_wait_at_most<MAXN>(n); }
 
 // LDS read issued as inline assembly so that the wait for it can be placed by hand: the
 // compiler's own placement waits for every outstanding LDS read, also the ones issued ahead
@@ -788,7 +789,12 @@ __device__ __forceinline__ void early_head_tile(
   const int ld_row = lane >> 2;
   const int ld_chunk = ((lane & 3) ^ ((lane >> 4) & 3)) << 4;  // byte offset in the global row
   const bool second_w = FN == 4 ? true : (FN == 2 ? false : wave < 4);
-  const int per_step = second_w ? 4 : 3;  // loads of this wave per K step
+  // Few score rows (a small batch): groups of 16 rows that lie wholly past the last row are
+  // not fetched at all, and a wave whose 64 rows lie past it neither reads fragments nor
+  // multiplies.  What such rows hold in LDS and in the accumulators is never looked at.
+  const bool a_on[2] = {m0 + 16 * wave < m_total, m0 + 16 * (wave + 8) < m_total};
+  const bool w_on = m0 + wm * 64 < m_total;
+  const int per_step = (a_on[0] ? 1 : 0) + (a_on[1] ? 1 : 0) + (second_w ? 2 : 1);  // loads of this wave per K step
   const unsigned char *a_src[2], *b_src[2];
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
@@ -803,7 +809,7 @@ __device__ __forceinline__ void early_head_tile(
     unsigned char *dst = gemm_smem + slot * kStageBytes + wave * 1024;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-      __builtin_amdgcn_global_load_lds((global_void *)a_src[j], (lds_void *)(dst + j * 8192), 16, 0, 0);
+      if (a_on[j]) __builtin_amdgcn_global_load_lds((global_void *)a_src[j], (lds_void *)(dst + j * 8192), 16, 0, 0);
       a_src[j] += kGemmRowBytes;
     }
     __builtin_amdgcn_global_load_lds((global_void *)b_src[0], (lds_void *)(dst + kGemmWOffset), 16, 0, 0);
@@ -863,23 +869,26 @@ __device__ __forceinline__ void early_head_tile(
     issue(slot_ld);
     slot_ld = slot_ld + 1 == kStages ? 0 : slot_ld + 1;
   }
-  gemm_wait_outstanding((n_pro - 1) * per_step);
+  constexpr int kMaxOutstanding = (kStages - 1) * 4;
+  gemm_wait_outstanding<kMaxOutstanding>((n_pro - 1) * per_step);
   __builtin_amdgcn_s_barrier();
   constexpr int kReads = 2 + FN;  // LDS reads of one half step
   Frag f0, f1;
-  read(f0, 0, 0);
+  if (w_on) read(f0, 0, 0);
   uint32_t so = 0;  // byte offset of the stage being multiplied
   for (int step = 0; step + 1 < n_steps; ++step) {
-    read(f1, so, 1);
-    gemm_wait_frag<kReads>(f0);  // the reads just issued fly while the MFMAs below run
-    mma(f0);
+    if (w_on) {
+      read(f1, so, 1);
+      gemm_wait_frag<kReads>(f0);  // the reads just issued fly while the MFMAs below run
+      mma(f0);
+    }
     __builtin_amdgcn_sched_barrier(0);
-    gemm_wait_frag<0>(f1);  // this wave is done with the slot of this step
+    if (w_on) gemm_wait_frag<0>(f1);  // this wave is done with the slot of this step
     // the next step has landed once at most the steps after it (kStages-2 of them were
     // issued) are outstanding
     {
       const int issued_after = n_steps - 2 - step < kStages - 2 ? n_steps - 2 - step : kStages - 2;
-      gemm_wait_outstanding(issued_after * per_step);
+      gemm_wait_outstanding<kMaxOutstanding>(issued_after * per_step);
     }
     __builtin_amdgcn_s_barrier();  // it is visible; every wave is done with this step's slot
     if (step + kStages < n_steps) {
@@ -887,15 +896,19 @@ __device__ __forceinline__ void early_head_tile(
       slot_ld = slot_ld + 1 == kStages ? 0 : slot_ld + 1;
     }
     so = so + kStageBytes == kStages * kStageBytes ? 0 : so + kStageBytes;
-    read(f0, so, 0);
-    mma(f1);
+    if (w_on) {
+      read(f0, so, 0);
+      mma(f1);
+    }
     __builtin_amdgcn_sched_barrier(0);
   }
-  read(f1, so, 1);
-  gemm_wait_frag<kReads>(f0);
-  mma(f0);
-  gemm_wait_frag<0>(f1);
-  mma(f1);
+  if (w_on) {
+    read(f1, so, 1);
+    gemm_wait_frag<kReads>(f0);
+    mma(f0);
+    gemm_wait_frag<0>(f1);
+    mma(f1);
+  }
 
   mfma_settle();
   if (KIND == 0)
@@ -903,6 +916,7 @@ __device__ __forceinline__ void early_head_tile(
   else
     epilogue_lse<FN>(acc, m0, v0, m_total, vocab, n_tile, wm, wn, lane, tb);
 }
+
 
 #include "early_head_tall.h"
 
