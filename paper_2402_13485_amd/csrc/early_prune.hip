@@ -918,6 +918,158 @@ __device__ __forceinline__ void early_head_tile(
 }
 
 
+
+// ------------------------------------------------------------------------------------
+// Few score rows (at most 128 in the whole batch: a small batch or small trees).  The
+// scoring kernel is then a stream of the weight matrix through the compute units, and a step
+// (a barrier, fragment reads whose latency a handful of matrix instructions cannot hide)
+// costs more than its bytes.  This tile takes 64-deep steps: half as many steps for the same
+// bytes, whole 128-byte lines from every row.  Same 128-wide column tile, wave layout, accumulator layout and epilogues as the
+// 256 x 128 tile above, of which only the upper 128 rows exist; LDS rows are 128 bytes, their
+// eight 16-byte chunks XOR-swizzled with key(row) = (row >> 1) & 7 (a fragment read takes rows
+// r .. r + 15 of one chunk column in one pass: two rows share a 256-byte bank line, eight keys
+// spread the eight pairs).
+// ------------------------------------------------------------------------------------
+constexpr int kSmallBM = 128, kSmallBK = 64, kSmallStages = 4;
+constexpr int kSmallRowBytes = kSmallBK * 2;                          // 128
+constexpr int kSmallWOffset = kSmallBM * kSmallRowBytes;              // 16 KB of score rows, then 16 KB of weight rows
+constexpr int kSmallStageBytes = 2 * kSmallWOffset;                   // 32 KB
+static_assert(kSmallStages * kSmallStageBytes <= kGemmLdsBytes, "ring");
+
+template <int KIND>
+__device__ __forceinline__ void early_head_small_tile(
+    int hidden, int vocab, int m_total, int v0, int n_tile,
+    const uint16_t *__restrict__ hidden_states, const uint16_t *__restrict__ head_weight,
+    const HeadTables &tb, unsigned char *gemm_smem) {
+  constexpr int FN = 2, BM = kGemmBM;
+  typedef __attribute__((address_space(3))) void lds_void;
+  typedef const __attribute__((address_space(1))) void global_void;
+  const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_void *)gemm_smem;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  const int l32 = lane & 31, g = lane >> 5;
+  int my_pos = 0, my_cc = 0;
+  if (KIND == 0 && tid < BM && tid < m_total) {
+    my_pos = tb.row_info[2 * tid];
+    my_cc = tb.row_info[2 * tid + 1];
+  }
+
+  // ---- loader: a load instruction fills 8 rows of 128 bytes (1 KB).  A stage has 16 such
+  //      groups of score rows and 16 of weight rows; wave w takes groups 2w and 2w + 1 of each.
+  //      Groups of score rows wholly past the last row are not fetched.
+  const int ld_row = lane >> 3, ld_pos = lane & 7;
+  const unsigned char *a_src[2], *b_src[2];
+  bool a_on[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int r = 8 * (2 * wave + j) + ld_row;  // row of the tile = LDS row
+    const int chunk = (ld_pos ^ ((r >> 1) & 7)) << 4;
+    a_on[j] = 8 * (2 * wave + j) < m_total;
+    const int m = r < m_total ? r : m_total - 1;
+    a_src[j] = reinterpret_cast<const unsigned char *>(hidden_states + (size_t)tb.row_src[m] * hidden) + chunk;
+    int v = v0 + r;
+    v = v < vocab ? v : vocab - 1;
+    b_src[j] = reinterpret_cast<const unsigned char *>(head_weight + (size_t)v * hidden) + chunk;
+  }
+  const int per_step = (a_on[0] ? 1 : 0) + (a_on[1] ? 1 : 0) + 2;  // loads of this wave per K step
+  const bool w_on = wm * 64 < m_total;                             // this wave's 64 rows hold score rows
+  auto issue = [&](int slot) {
+    unsigned char *dst = gemm_smem + slot * kSmallStageBytes + wave * 2048;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      if (a_on[j]) __builtin_amdgcn_global_load_lds((global_void *)a_src[j], (lds_void *)(dst + j * 1024), 16, 0, 0);
+      a_src[j] += kSmallRowBytes;
+      __builtin_amdgcn_global_load_lds((global_void *)b_src[j], (lds_void *)(dst + kSmallWOffset + j * 1024), 16, 0, 0);
+      b_src[j] += kSmallRowBytes;
+    }
+  };
+
+  // ---- per-lane LDS read addresses: operand row l32 of a 32-row block (the key of row + 32 is
+  //      the key of the row), chunk 2 * ks + g for the K sub-step ks of 16
+  uint32_t a_rd[4], b_rd[4];
+  {
+    const int key = (l32 >> 1) & 7;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const int off = l32 * kSmallRowBytes + (((2 * ks + g) ^ key) << 4);
+      a_rd[ks] = smem_base + wm * 64 * kSmallRowBytes + off;
+      b_rd[ks] = smem_base + kSmallWOffset + wn * 64 * kSmallRowBytes + off;
+    }
+  }
+  typedef GemmFrag<FN> Frag;
+  auto read = [&](Frag &f, uint32_t so, int ks) {
+    const uint32_t pa = a_rd[ks] + so, pb = b_rd[ks] + so;
+    f.a[0] = gemm_lds_read16<0>(pa);
+    f.a[1] = gemm_lds_read16<32 * kSmallRowBytes>(pa);
+    f.b[0] = gemm_lds_read16<0>(pb);
+    f.b[1] = gemm_lds_read16<32 * kSmallRowBytes>(pb);
+  };
+  f32x16 acc[2][FN];
+#pragma unroll
+  for (int x = 0; x < 2; ++x)
+#pragma unroll
+    for (int y = 0; y < FN; ++y)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
+  auto mma = [&](const Frag &f) {
+#pragma unroll
+    for (int x = 0; x < 2; ++x)
+#pragma unroll
+      for (int y = 0; y < FN; ++y)
+        acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+            __builtin_bit_cast(bf16x8, f.a[x]), __builtin_bit_cast(bf16x8, f.b[y]), acc[x][y], 0, 0, 0);
+  };
+
+  const int n_steps = hidden / kSmallBK;
+  const int n_pro = n_steps < kSmallStages ? n_steps : kSmallStages;
+  constexpr int kMaxOutstanding = (kSmallStages - 1) * 4;
+  int slot_ld = 0;
+  for (int i = 0; i < n_pro; ++i) {
+    issue(slot_ld);
+    slot_ld = slot_ld + 1 == kSmallStages ? 0 : slot_ld + 1;
+  }
+  gemm_wait_outstanding<kMaxOutstanding>((n_pro - 1) * per_step);
+  __builtin_amdgcn_s_barrier();
+  constexpr int kReads = 2 + FN;  // LDS reads of one K sub-step
+  Frag f0, f1;
+  if (w_on) read(f0, 0, 0);
+  uint32_t so = 0;  // byte offset of the stage being multiplied
+  for (int step = 0; step < n_steps; ++step) {
+    if (w_on) {
+      read(f1, so, 1);
+      gemm_wait_frag<kReads>(f0);  // the reads just issued fly while the MFMAs below run
+      mma(f0);
+      read(f0, so, 2);
+      gemm_wait_frag<kReads>(f1);
+      mma(f1);
+      read(f1, so, 3);
+      gemm_wait_frag<kReads>(f0);
+      mma(f0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (w_on) gemm_wait_frag<0>(f1);  // this wave is done with the slot of this step
+    if (step + 1 < n_steps) {
+      const int issued_after = n_steps - 2 - step < kSmallStages - 2 ? n_steps - 2 - step : kSmallStages - 2;
+      gemm_wait_outstanding<kMaxOutstanding>(issued_after * per_step);
+      __builtin_amdgcn_s_barrier();  // it is visible; every wave is done with this step's slot
+      if (step + kSmallStages < n_steps) {
+        issue(slot_ld);  // into the slot of this step
+        slot_ld = slot_ld + 1 == kSmallStages ? 0 : slot_ld + 1;
+      }
+      so = so + kSmallStageBytes == kSmallStages * kSmallStageBytes ? 0 : so + kSmallStageBytes;
+      if (w_on) read(f0, so, 0);
+    }
+    if (w_on) mma(f1);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  mfma_settle();
+  if (KIND == 0)
+    epilogue_count<FN>(acc, 0, v0, n_tile, vocab, tid, my_pos, my_cc, tb, gemm_smem);
+  else
+    epilogue_lse<FN>(acc, 0, v0, m_total, vocab, n_tile, wm, wn, lane, tb);
+}
+
 #include "early_head_tall.h"
 
 // Which tile shape a call uses: decided on the device by every workgroup (and by the kernels
@@ -980,7 +1132,9 @@ __global__ __launch_bounds__(kGemmThreads, 1) void early_head_bf16_kernel(
       continue;
     }
     const int m0 = m_tile * kGemmBM, v0 = n_tile * 64 * pl.fn;
-    if (pl.fn == 2)
+    if (pl.fn == 2 && m_total <= kSmallBM && hidden % kSmallBK == 0)
+      early_head_small_tile<KIND>(hidden, vocab, m_total, v0, n_tile, hidden_states, head_weight, tb, gemm_smem);
+    else if (pl.fn == 2)
       early_head_tile<2, KIND>(hidden, vocab, m_total, m0, v0, n_tile, hidden_states, head_weight, tb, gemm_smem);
     else if (pl.fn == 3)
       early_head_tile<3, KIND>(hidden, vocab, m_total, m0, v0, n_tile, hidden_states, head_weight, tb, gemm_smem);
