@@ -772,7 +772,12 @@ __device__ __forceinline__ void early_head_tile(
   typedef const __attribute__((address_space(1))) void global_void;
   const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_void *)gemm_smem;
 
-  const int tid = threadIdx.x, lane = tid & 63;
+  // The thread id is made opaque: what is derived from it (addresses, row and chunk numbers)
+  // is then computed here, inside the loop over tiles, and not hoisted out of that loop into
+  // registers that stay occupied while the other tile shapes run.
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));
+  const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
   const int l32 = lane & 31, g = lane >> 5;
@@ -945,7 +950,12 @@ __device__ __forceinline__ void early_head_small_tile(
   typedef __attribute__((address_space(3))) void lds_void;
   typedef const __attribute__((address_space(1))) void global_void;
   const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_void *)gemm_smem;
-  const int tid = threadIdx.x, lane = tid & 63;
+  // The thread id is made opaque: what is derived from it (addresses, row and chunk numbers)
+  // is then computed here, inside the loop over tiles, and not hoisted out of that loop into
+  // registers that stay occupied while the other tile shapes run.
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));
+  const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
   const int l32 = lane & 31, g = lane >> 5;
