@@ -543,6 +543,67 @@ def test_whole_step_reduced_c3(pb, oracle):
     assert (to_host(nxt) == r_next).all()
 
 
+def test_whole_step_replayed_from_a_captured_graph(pb):
+    """The four calls of a step enqueue kernels only (no allocation of their own when the
+    caller passes workspaces, no memset, no host round trip), so a step can be captured into a
+    HIP graph.  Replayed three times, with eager steps and synchronisations in between, every
+    replay must give the eager step's results bit for bit."""
+    w = synth.Workload(3, "c3_reduced", "bf16", 3, 4, 128, 64, 512, 4096, 10, 1e-3)
+    trees = [synth.rank_product_tree(64, 4)] * 3
+    seq = np.array([700, 512, 1031], np.int32)
+    xa = synth.make_attention_inputs(w, seq_lens=seq, trees=trees)
+    xp = synth.make_prune_inputs(w, trees=trees)
+    acc = synth.make_accept_inputs(w, xp["n_nodes"], xp["parent"], xp["token"])
+    tree = dev_tree(pb, xp["n_nodes"], xp["parent"], xp["token"])
+    d = {k: to_dev(xa[k]) for k in ("q", "k_cache", "v_cache", "k_tree", "v_tree")}
+    seq_d, hid, hw, logits = to_dev(seq), to_dev(xp["hidden_states"]), to_dev(xp["head_weight"]), to_dev(acc["logits"])
+    B, H, T, dd = xa["q"].shape
+    ws_att = torch.empty(pb.workspace_bytes(pb.WS_TREE_ATTENTION, B, T, H, dd, xa["L_max"]), dtype=torch.uint8, device="cuda")
+    ws_pr = torch.empty(pb.workspace_bytes(pb.WS_EARLY_PRUNE, B, T, hidden=512, vocab=4096), dtype=torch.uint8, device="cuda")
+    ws_acc = torch.empty(pb.workspace_bytes(pb.WS_ACCEPT_PATH, B, T, vocab=4096), dtype=torch.uint8, device="cuda")
+    payloads = [d["q"], d["k_tree"], d["v_tree"], logits]
+
+    def step():
+        out_full = pb.propd_tree_attention(tree, d["q"], d["k_cache"], d["v_cache"], d["k_tree"], d["v_tree"],
+                                           seq_d, xa["scale"], workspace=ws_att)
+        res = pb.propd_early_prune(tree, hid, hw, 10, payloads=payloads, workspace=ws_pr)
+        q2, kt2, vt2, lg2 = res.payloads
+        out_small = torch.zeros_like(d["q"])
+        pb.propd_tree_attention(res.tree, q2, d["k_cache"], d["v_cache"], kt2, vt2, seq_d, xa["scale"],
+                                out=out_small, workspace=ws_att)
+        alen, path, nxt = pb.propd_accept_path(res.tree, lg2, workspace=ws_acc)
+        return [out_full, res.keep_bits, res.new_index, res.orig_index, res.n_kept, res.cu_nodes, res.tree.parent,
+                res.tree.anc, out_small, alen, path, nxt]
+
+    eager = [t.clone() for t in step()]
+    torch.cuda.synchronize()
+    kept = to_host(eager[4])
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        outs = step()
+    for _ in range(3):
+        again = step()                      # eager work between the replays
+        torch.cuda.synchronize()
+        for t in outs:
+            t.fill_(0) if t.dtype != torch.bfloat16 else t.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name_i, (got, want, eag) in enumerate(zip(outs, eager, again)):
+            g, e = to_host(got), to_host(want)
+            if name_i == 0:               # full-tree attention: rows of the tree only
+                for b in range(B):
+                    Tb = int(xp["n_nodes"][b])
+                    assert (g[b, :, :Tb] == e[b, :, :Tb]).all()
+            elif name_i == 8:             # compacted-tree attention: survivors' rows only
+                for b in range(B):
+                    assert (g[b, :, :kept[b]] == e[b, :, :kept[b]]).all()
+            else:
+                assert (g == e).all(), name_i
+            assert (to_host(eag) == e).all() or name_i in (0, 8)
+
+
 def test_layers_before_and_after_the_pruning_point(pb, oracle):
     """Figure 5 at reduced size: two layers of tree attention on the full tree, the pruning pass,
     two layers on the compacted tree, acceptance; every layer has its own K/V cache and its own
