@@ -209,11 +209,12 @@ def main() -> int:
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step_eager = wall * 1e3 / args.steps
-    ms_per_step, launch = ms_per_step_eager, "eager"
+    ms_per_step, launch, ms_per_step_graph = ms_per_step_eager, "eager", None
     if not args.eager:
         # One step captured on a side stream (default priority) and replayed: W untimed replays,
         # then exactly K between two synchronisations.  The eager pass above supplies the parts.
         try:
+            eager_host = [to_host(t) for t in last]
             side = torch.cuda.Stream()
             graph = torch.cuda.CUDAGraph()
             with torch.cuda.graph(graph, stream=side):
@@ -225,8 +226,14 @@ def main() -> int:
             for _ in range(args.steps):
                 graph.replay()
             torch.cuda.synchronize()
-            ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
-            launch = "hip_graph_replay"
+            if not all((to_host(a) == b).all() for a, b in zip(last, eager_host)):
+                raise RuntimeError("the replayed step's accepted paths differ from the eager step's")
+            ms_per_step_graph = (time.perf_counter() - t0) * 1e3 / args.steps
+            if ms_per_step_graph < ms_per_step_eager:
+                ms_per_step, launch = ms_per_step_graph, "hip_graph_replay"
+            else:
+                log(f"replays took {ms_per_step_graph:.4f} ms per step, eager launches {ms_per_step_eager:.4f}: "
+                    "reporting the eager steps")
         except Exception as e:  # capture is an optimisation of the launch path, not a requirement
             log(f"graph capture failed ({type(e).__name__}: {e}); reporting the eager steps")
             torch.cuda.synchronize()
@@ -284,6 +291,7 @@ def main() -> int:
         "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "ms_per_step_eager": ms_per_step_eager,
+        "ms_per_step_graph": ms_per_step_graph,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "B": B, "H": H, "d": d, "L_max": L_max, "T_max": T_max,
